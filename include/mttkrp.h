@@ -1,0 +1,148 @@
+/*
+ * mttkrp.h -- C ABI of the MI355X (gfx950) matrix-free dense MTTKRP library.
+ *
+ * The one operation behind every entry point is the mode-k matricized-tensor
+ * times Khatri-Rao product in its element-wise ("matrix-free") form, paper
+ * Sec. II-B, Eq. (elem), with the weight vector lambda fixed to one:
+ *
+ *     M(n, j) = sum_{i : i_k = n}  X(i) * prod_{m != k} A_m(i_m, j),
+ *               n in [0, I_k),  j in [0, R),
+ *
+ * which equals X_(k) * (A_d (.) ... (.) A_{k+1} (.) A_{k-1} (.) ... (.) A_1) of
+ * Eq. (krp) without ever forming the Khatri-Rao matrix or an unfolded or
+ * permuted copy of X.  Extra device memory is O(R * sum_n I_n)-class partial
+ * sums only (Sec. I, contributions; Sec. II-B last paragraph).
+ *
+ * Layouts (Sec. II-A: ind2sub/sub2ind "defined like MATLAB" => first index
+ * fastest; Sec. III: row-wise factor layout):
+ *   X          dense, flat, no padding, first index fastest:
+ *              X[i_0 + I_0*(i_1 + I_1*(i_2 + ...))]
+ *   factors[m] row-major I_m x R, leading dimension R
+ *   M          row-major I_k x R, leading dimension R
+ * Indices and k are 0-based in this interface (the paper counts from 1).
+ *
+ * Pointers: X, every factors[m], M and workspace are DEVICE pointers owned by
+ * the caller.  dims and the factors pointer array are HOST arrays, read before
+ * the call returns.  The library keeps no reference to any argument after the
+ * call returns (the enqueued kernels do, until the stream has drained).
+ * stream is a hipStream_t passed as void* (NULL = the default stream).
+ *
+ * Semantics: M is overwritten (never accumulated into).  factors[k] is never
+ * read and may be NULL (Eq. (elem) excludes m = k).  M must not alias an
+ * input.  Calls are asynchronous: they return after enqueueing on stream.
+ *
+ * Errors: every function returns an mttkrp_status (or documents otherwise),
+ * never throws, aborts or exits.  On any error nothing is enqueued and M is
+ * untouched.
+ *   MTTKRP_ERR_INVALID_ARG  null X/M/dims/factors, null factors[m != k],
+ *                           ndim < 2, dims[m] < 1, R < 1, k out of range,
+ *                           element count or byte size overflowing int64
+ *   MTTKRP_ERR_UNSUPPORTED  ndim > MTTKRP_MAX_NDIM, a dimension or R >= 2^31,
+ *                           or a decomposition that would need >= 2^31 work
+ *                           items
+ *   MTTKRP_ERR_WORKSPACE    a *_ws call with too few workspace bytes, or
+ *                           workspace not 256-byte aligned
+ *   MTTKRP_ERR_DEVICE       a HIP runtime call failed
+ */
+#ifndef MTTKRP_H
+#define MTTKRP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MTTKRP_MAX_NDIM 8
+
+typedef enum {
+    MTTKRP_OK = 0,
+    MTTKRP_ERR_INVALID_ARG = 1,
+    MTTKRP_ERR_UNSUPPORTED = 2,
+    MTTKRP_ERR_WORKSPACE = 3,
+    MTTKRP_ERR_DEVICE = 4
+} mttkrp_status;
+
+/*
+ * Core calls, Eq. (elem): M = X_(k) (Khatri-Rao of all A_m, m != k), one per
+ * data type.  Partial sums live in a library-owned per-device workspace that
+ * grows on demand; growing it is the only time these calls allocate (and
+ * synchronise the device).
+ *   ndim     number of modes d, 2 <= d <= MTTKRP_MAX_NDIM
+ *   dims     host array of d extents I_0..I_{d-1}, each >= 1
+ *   X        device, prod(dims) values
+ *   factors  host array of d device pointers; factors[m] is I_m x R
+ *   R        number of columns (rank), any R >= 1
+ *   k        mode, 0 <= k < d
+ *   M        device, I_k x R, overwritten
+ */
+int mttkrp_dense_f64(int ndim, const int64_t* dims, const double* X,
+                     const double* const* factors, int R, int k, double* M,
+                     void* stream);
+int mttkrp_dense_f32(int ndim, const int64_t* dims, const float* X,
+                     const float* const* factors, int R, int k, float* M,
+                     void* stream);
+
+/*
+ * Caller-owned workspace variants of the same operation.  They never allocate.
+ * mttkrp_dense_workspace_bytes returns the bytes the *_ws call with the same
+ * (ndim, dims, R, k, dtype_bytes in {8, 4}) needs (possibly 0), or
+ * (size_t)-1 for invalid arguments.  workspace must be a device pointer
+ * aligned to 256 bytes (NULL allowed when 0 bytes are needed); its previous
+ * contents do not matter and it holds no result after the call.
+ */
+size_t mttkrp_dense_workspace_bytes(int ndim, const int64_t* dims, int R, int k,
+                                    int dtype_bytes);
+int mttkrp_dense_f64_ws(int ndim, const int64_t* dims, const double* X,
+                        const double* const* factors, int R, int k, double* M,
+                        void* workspace, size_t workspace_bytes, void* stream);
+int mttkrp_dense_f32_ws(int ndim, const int64_t* dims, const float* X,
+                        const float* const* factors, int R, int k, float* M,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Static, human-readable text for a status code. */
+const char* mttkrp_status_string(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int mttkrp_version(void);
+
+/* Frees the library-owned workspaces of every device (synchronises them). */
+void mttkrp_release(void);
+
+/*
+ * Measurement hooks (Sec. IV-B reports time per MTTKRP).  With timing enabled
+ * every core / *_ws call records HIP events on its stream around its streaming
+ * kernel and around its combine kernel.  mttkrp_timing_last waits for those
+ * events and returns the two durations in milliseconds of the most recent
+ * call on the current device (combine_ms = 0 when no combine kernel ran).
+ * Returns MTTKRP_ERR_INVALID_ARG if nothing was recorded.
+ */
+int mttkrp_timing_enable(int enable);
+int mttkrp_timing_last(float* stream_ms, float* combine_ms);
+
+/*
+ * Decomposition parameters for tuning sweeps and schedule-invariance tests
+ * (the result of Eq. (elem) must not depend on them beyond rounding).
+ * 0 restores the built-in choice.  Keys:
+ *   "row_blocks"    16-row MFMA blocks per wavefront (1..4)
+ *   "target_items"  wavefront work items the planner aims for
+ *   "max_steps"     upper bound on 4-column steps per work item
+ *   "xcd_remap"     1 = contiguous item ranges per XCD, 2 = plain order
+ *   "ws_percent"    cap on first-mode partial-sum traffic, percent of X bytes
+ * Returns MTTKRP_ERR_INVALID_ARG for an unknown key or a value out of range.
+ */
+int mttkrp_tune_set(const char* key, int64_t value);
+
+/*
+ * Writes a one-line description of the decomposition the library would use
+ * (row blocks, column blocks, work items, steps per item, partial slots,
+ * workspace bytes) into buf (always NUL-terminated when buflen > 0).
+ */
+int mttkrp_plan_describe(int ndim, const int64_t* dims, int R, int k,
+                         int dtype_bytes, char* buf, size_t buflen);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MTTKRP_H */

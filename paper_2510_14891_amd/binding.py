@@ -1,0 +1,208 @@
+"""Thin ctypes binding of the C-ABI library ``libmttkrp_hip.so``.
+
+Argument marshalling only: every step of the MTTKRP runs in the HIP kernels of
+``csrc/mttkrp.hip``.  PyTorch appears here solely as the owner of device memory
+and of the HIP stream.  There is no CPU fallback: if the library has not been
+built (``python -m paper_2510_14891_amd.build``) every entry point raises.
+Function names follow ``include/mttkrp.h``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmttkrp_hip.so")
+
+MTTKRP_OK = 0
+MTTKRP_ERR_INVALID_ARG = 1
+MTTKRP_ERR_UNSUPPORTED = 2
+MTTKRP_ERR_WORKSPACE = 3
+MTTKRP_ERR_DEVICE = 4
+MTTKRP_MAX_NDIM = 8
+
+# every symbol include/mttkrp.h declares
+EXPORTED = (
+    "mttkrp_dense_f64", "mttkrp_dense_f32", "mttkrp_dense_workspace_bytes",
+    "mttkrp_dense_f64_ws", "mttkrp_dense_f32_ws", "mttkrp_status_string",
+    "mttkrp_version", "mttkrp_release", "mttkrp_timing_enable",
+    "mttkrp_timing_last", "mttkrp_tune_set", "mttkrp_plan_describe",
+)
+
+_lib = None
+
+
+class MttkrpError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__("mttkrp: %s (status %d)" % (text, status))
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """Load the library once; raise loudly if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "HIP library %s is missing: build it with "
+            "`python -m paper_2510_14891_amd.build` (there is no CPU fallback)" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    vpp = ctypes.POINTER(ctypes.c_void_p)
+    core = [ctypes.c_int, i64p, ctypes.c_void_p, vpp, ctypes.c_int, ctypes.c_int,
+            ctypes.c_void_p, ctypes.c_void_p]
+    core_ws = core[:-1] + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    for name in ("mttkrp_dense_f64", "mttkrp_dense_f32"):
+        getattr(L, name).restype = ctypes.c_int
+        getattr(L, name).argtypes = core
+    for name in ("mttkrp_dense_f64_ws", "mttkrp_dense_f32_ws"):
+        getattr(L, name).restype = ctypes.c_int
+        getattr(L, name).argtypes = core_ws
+    L.mttkrp_dense_workspace_bytes.restype = ctypes.c_size_t
+    L.mttkrp_dense_workspace_bytes.argtypes = [ctypes.c_int, i64p, ctypes.c_int,
+                                               ctypes.c_int, ctypes.c_int]
+    L.mttkrp_status_string.restype = ctypes.c_char_p
+    L.mttkrp_status_string.argtypes = [ctypes.c_int]
+    L.mttkrp_version.restype = ctypes.c_int
+    L.mttkrp_release.restype = None
+    L.mttkrp_timing_enable.restype = ctypes.c_int
+    L.mttkrp_timing_enable.argtypes = [ctypes.c_int]
+    L.mttkrp_timing_last.restype = ctypes.c_int
+    L.mttkrp_timing_last.argtypes = [ctypes.POINTER(ctypes.c_float),
+                                     ctypes.POINTER(ctypes.c_float)]
+    L.mttkrp_tune_set.restype = ctypes.c_int
+    L.mttkrp_tune_set.argtypes = [ctypes.c_char_p, ctypes.c_int64]
+    L.mttkrp_plan_describe.restype = ctypes.c_int
+    L.mttkrp_plan_describe.argtypes = [ctypes.c_int, i64p, ctypes.c_int, ctypes.c_int,
+                                       ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
+    _lib = L
+    return L
+
+
+def mttkrp_status_string(status: int) -> str:
+    return lib().mttkrp_status_string(int(status)).decode()
+
+
+def _check(status: int) -> None:
+    if status != MTTKRP_OK:
+        raise MttkrpError(status, mttkrp_status_string(status))
+
+
+def mttkrp_version() -> int:
+    return int(lib().mttkrp_version())
+
+
+def mttkrp_release() -> None:
+    lib().mttkrp_release()
+
+
+def mttkrp_timing_enable(enable: bool) -> None:
+    _check(lib().mttkrp_timing_enable(1 if enable else 0))
+
+
+def mttkrp_timing_last():
+    """(stream_ms, combine_ms) of the most recent call on the current device."""
+    a, b = ctypes.c_float(0), ctypes.c_float(0)
+    _check(lib().mttkrp_timing_last(ctypes.byref(a), ctypes.byref(b)))
+    return float(a.value), float(b.value)
+
+
+def mttkrp_tune_set(key: str, value: int) -> None:
+    _check(lib().mttkrp_tune_set(key.encode(), int(value)))
+
+
+def _dims_array(dims: Sequence[int]):
+    return (ctypes.c_int64 * len(dims))(*[int(v) for v in dims])
+
+
+def mttkrp_plan_describe(dims: Sequence[int], R: int, k: int, dtype_bytes: int) -> str:
+    buf = ctypes.create_string_buffer(512)
+    _check(lib().mttkrp_plan_describe(len(dims), _dims_array(dims), int(R), int(k),
+                                      int(dtype_bytes), buf, len(buf)))
+    return buf.value.decode()
+
+
+def mttkrp_dense_workspace_bytes(dims: Sequence[int], R: int, k: int, dtype_bytes: int) -> int:
+    n = lib().mttkrp_dense_workspace_bytes(len(dims), _dims_array(dims), int(R), int(k),
+                                           int(dtype_bytes))
+    if n == ctypes.c_size_t(-1).value:
+        raise MttkrpError(MTTKRP_ERR_INVALID_ARG, "invalid argument")
+    return int(n)
+
+
+def mttkrp_dense(X, dims: Sequence[int], factors: Sequence, k: int, M=None,
+                 workspace=None, stream: Optional[int] = None):
+    """M = X_(k) (Khatri-Rao of all factors but the k-th), on the GPU.
+
+    X        flat torch tensor on a HIP device, prod(dims) values, first index
+             fastest; float64 or float32
+    dims     extents (I_0, ..., I_{d-1})
+    factors  d torch tensors, factors[m] of shape (I_m, R), contiguous, same
+             dtype/device as X; factors[k] may be None
+    k        0-based mode
+    M        optional output tensor (I_k, R); allocated when None
+    workspace  optional torch tensor to use as caller-owned workspace (selects
+             the *_ws entry point)
+    stream   raw hipStream_t value; default: torch's current stream
+    Returns M.  The call is asynchronous on the stream.
+    """
+    import torch
+    L = lib()
+    if not X.is_cuda:
+        raise ValueError("X must live on the GPU")
+    if X.dtype == torch.float64:
+        suffix, sbytes = "f64", 8
+    elif X.dtype == torch.float32:
+        suffix, sbytes = "f32", 4
+    else:
+        raise TypeError("X must be float64 or float32")
+    d = len(dims)
+    if not X.is_contiguous():
+        raise ValueError("X must be contiguous (flat, first index fastest)")
+    n = 1
+    for v in dims:
+        n *= int(v)
+    if X.numel() != n:
+        raise ValueError("X has %d values, dims say %d" % (X.numel(), n))
+    if len(factors) != d:
+        raise ValueError("need one factor slot per mode")
+    R = None
+    ptrs = (ctypes.c_void_p * d)()
+    for m in range(d):
+        A = factors[m]
+        if A is None:
+            ptrs[m] = None
+            continue
+        if A.dtype != X.dtype or A.device != X.device or not A.is_contiguous():
+            raise ValueError("factor %d: wrong dtype/device or not contiguous" % m)
+        if A.dim() != 2 or A.shape[0] != int(dims[m]):
+            raise ValueError("factor %d has shape %s" % (m, tuple(A.shape)))
+        if R is None:
+            R = int(A.shape[1])
+        elif int(A.shape[1]) != R:
+            raise ValueError("factors disagree on R")
+        ptrs[m] = A.data_ptr()
+    if R is None:
+        raise ValueError("no factor given")
+    if M is None:
+        M = torch.empty((int(dims[k]), R), dtype=X.dtype, device=X.device)
+    else:
+        if (M.dtype != X.dtype or M.device != X.device or not M.is_contiguous()
+                or tuple(M.shape) != (int(dims[k]), R)):
+            raise ValueError("M must be a contiguous (I_k, R) tensor like X")
+    if stream is None:
+        stream = torch.cuda.current_stream(X.device).cuda_stream
+    with torch.cuda.device(X.device):
+        if workspace is None:
+            rc = getattr(L, "mttkrp_dense_" + suffix)(
+                d, _dims_array(dims), X.data_ptr(), ptrs, R, int(k), M.data_ptr(),
+                ctypes.c_void_p(stream))
+        else:
+            rc = getattr(L, "mttkrp_dense_" + suffix + "_ws")(
+                d, _dims_array(dims), X.data_ptr(), ptrs, R, int(k), M.data_ptr(),
+                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                ctypes.c_void_p(stream))
+    _check(rc)
+    return M

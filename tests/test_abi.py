@@ -1,0 +1,81 @@
+"""Host-side checks of the C-ABI library: it loads, it exports every symbol the
+header declares, and its argument validation and planning arithmetic (which
+need no GPU) behave as the header says.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mttkrp.h")
+
+
+@pytest.fixture(scope="module")
+def mt():
+    from paper_2510_14891_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    binding.lib()
+    return binding
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mttkrp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(mt):
+    names = declared_functions()
+    assert len(names) >= 12
+    L = mt.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(mt.EXPORTED) == names
+
+
+def test_status_strings_and_version(mt):
+    assert mt.mttkrp_version() >= 100
+    seen = set()
+    for s in range(5):
+        t = mt.mttkrp_status_string(s)
+        assert t and t not in seen
+        seen.add(t)
+    assert "unknown" in mt.mttkrp_status_string(99)
+
+
+def test_workspace_query_and_validation(mt):
+    L = mt.lib()
+    bad = ctypes.c_size_t(-1).value
+    d3 = (ctypes.c_int64 * 3)(64, 64, 64)
+    assert L.mttkrp_dense_workspace_bytes(3, d3, 16, 0, 8) != bad
+    assert L.mttkrp_dense_workspace_bytes(3, d3, 16, 3, 8) == bad      # k out of range
+    assert L.mttkrp_dense_workspace_bytes(3, d3, 0, 0, 8) == bad       # R < 1
+    assert L.mttkrp_dense_workspace_bytes(1, d3, 4, 0, 8) == bad       # ndim < 2
+    assert L.mttkrp_dense_workspace_bytes(3, d3, 4, 0, 2) == bad       # dtype size
+    assert L.mttkrp_dense_workspace_bytes(3, None, 4, 0, 8) == bad
+    z = (ctypes.c_int64 * 3)(64, 0, 64)
+    assert L.mttkrp_dense_workspace_bytes(3, z, 4, 0, 8) == bad
+    huge = (ctypes.c_int64 * 3)(2 ** 30, 2 ** 30, 2 ** 30)            # N overflows
+    assert L.mttkrp_dense_workspace_bytes(3, huge, 4, 0, 8) == bad
+    # null pointers are rejected before anything touches the device
+    assert L.mttkrp_dense_f64(3, d3, None, None, 4, 0, None, None) == mt.MTTKRP_ERR_INVALID_ARG
+    assert L.mttkrp_tune_set(b"no_such_key", 1) == mt.MTTKRP_ERR_INVALID_ARG
+    assert L.mttkrp_tune_set(b"row_blocks", 9) == mt.MTTKRP_ERR_INVALID_ARG
+
+
+def test_workspace_stays_in_the_sum_of_dims_class(mt):
+    """Sec. I / II-B: memory beyond X is O(R sum_n I_n)-class, never
+    O(R prod_{n != k} I_n).  The partial sums are (number of splits) x I_k x R
+    with the split count bounded by a plan constant."""
+    from paper_2510_14891_amd import inputs
+    for name, w in inputs.WORKLOADS.items():
+        for k in range(w.ndim):
+            ws = mt.mttkrp_dense_workspace_bytes(w.dims, w.R, k, w.itemsize)
+            x_bytes = w.numel * w.itemsize
+            assert ws <= 0.04 * x_bytes + (64 << 20), (name, k, ws)
+            desc = mt.mttkrp_plan_describe(w.dims, w.R, k, w.itemsize)
+            slots = int(re.search(r"slots=(\d+)", desc).group(1))
+            assert ws == (slots * w.dims[k] * w.R * w.itemsize if slots > 1 else 0)
+            assert slots <= 4096, (name, k, slots)

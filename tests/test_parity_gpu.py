@@ -1,0 +1,260 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle.
+
+Every case draws seeded inputs from ``paper_2510_14891_amd.inputs``, runs the
+library on the GPU and the oracle on the host on the same buffers, and compares
+with the normwise relative error ||M_gpu - M_orc||_F / ||M_orc||_F:
+<= 1e-12 for fp64, <= 1e-5 for fp32.  Any re-association of the sum in
+Eq. (elem) is a correct result, so parity is by norm, not by bits; what must be
+bit-identical is a rerun of the same call (fixed-order combine, no atomics).
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_2510_14891_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float64: 1e-12, torch.float32: 1e-5}
+
+
+@pytest.fixture(scope="module")
+def mt():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2510_14891_amd import binding
+    binding.lib()   # raises if the HIP library was not built: no silent fallback
+    yield binding
+    for key in ("row_blocks", "target_items", "max_steps", "xcd_remap", "ws_percent"):
+        binding.mttkrp_tune_set(key, 0)
+
+
+def make_problem(dims, R, dtype, seed, dist=("uniform", -1.0, 1.0)):
+    """Flat X (first index fastest) and factors, on the host."""
+    n = int(np.prod(dims))
+    if dist[0] == "uniform":
+        X = inputs.uniform(seed, n, dist[1], dist[2], dtype=dtype)
+        A = [inputs.uniform(seed + 100 + m, (I, R), dist[1], dist[2], dtype=dtype)
+             for m, I in enumerate(dims)]
+    else:
+        X = inputs.normal(seed, n, dist[1], dist[2], dtype=dtype)
+        A = [inputs.normal(seed + 100 + m, (I, R), dist[1], dist[2], dtype=dtype)
+             for m, I in enumerate(dims)]
+    return X, A
+
+
+def gpu_mttkrp(mt, X, dims, A, k, **kw):
+    Xd = X.cuda()
+    Ad = [a.cuda() if a is not None else None for a in A]
+    M = mt.mttkrp_dense(Xd, dims, Ad, k, **kw)
+    torch.cuda.synchronize()
+    return M.cpu().numpy()
+
+
+def oracle_mttkrp(oracle, X, dims, A, k, rows=None):
+    Xn = inputs.as_ndarray_view(X, dims)
+    An = [a.numpy() if a is not None else None for a in A]
+    return oracle.mttkrp(Xn, An, k, rows=rows)
+
+
+def check_all_modes(mt, oracle, dims, R, dtype, seed, dist=("uniform", -1.0, 1.0)):
+    X, A = make_problem(dims, R, dtype, seed, dist)
+    worst = 0.0
+    for k in range(len(dims)):
+        print("case dims=%s R=%d %s k=%d seed=%d" % (dims, R, dtype, k, seed), flush=True)
+        got = gpu_mttkrp(mt, X, dims, A, k)
+        ref = oracle_mttkrp(oracle, X, dims, A, k)
+        err = oracle.normwise_rel_err(got, ref)
+        worst = max(worst, err)
+        assert err <= TOL[dtype], (dims, R, k, err)
+    return worst
+
+
+# ---------------------------------------------------------------- small shapes, every mode
+SMALL = [
+    # dims, R  -- several 64-row tiles plus a ragged tail, odd inner sizes, tiny modes
+    ((64, 64, 64), 16),          # benchmark configuration 1 exactly
+    ((150, 37, 21), 16),
+    ((70, 9, 5, 7), 5),
+    ((33, 6, 4, 3, 5), 33),
+    ((5, 300), 7),
+    ((300, 5), 7),
+    ((1, 7, 9), 3),
+    ((17, 1, 1, 40), 4),
+    ((16, 16, 16), 1),
+    ((129, 13, 12), 17),
+    ((48, 10, 6, 5), 64),
+    ((40, 11, 9), 100),
+    ((3, 2, 2, 2, 2, 2, 2, 3), 6),
+    ((200, 3, 2), 2),
+    ((2, 2), 1),
+    ((15, 15, 15), 48),
+]
+
+
+@pytest.mark.parametrize("dims,R", SMALL)
+def test_small_fp64(mt, oracle, dims, R):
+    check_all_modes(mt, oracle, dims, R, torch.float64, seed=7)
+
+
+@pytest.mark.parametrize("dims,R", SMALL)
+def test_small_fp32(mt, oracle, dims, R):
+    check_all_modes(mt, oracle, dims, R, torch.float32, seed=8)
+
+
+def test_config1_recipe(mt, oracle):
+    """Benchmark configuration 1 with its own recipe (U[0,1) data, seeds)."""
+    w = inputs.WORKLOADS["c1_64x64x64_f64_R16"]
+    X = inputs.make_tensor(w)
+    A = inputs.make_factors(w)
+    for k in range(3):
+        got = gpu_mttkrp(mt, X, w.dims, A, k)
+        ref = oracle_mttkrp(oracle, X, w.dims, A, k)
+        assert oracle.normwise_rel_err(got, ref) <= 1e-12
+
+
+# ---------------------------------------------------------------- scaled-down configurations 2-5
+SCALED = [
+    ("c2_1024x1024x512_f64_R32", (256, 128, 96), None),
+    ("c3_192x192x192x192_f64_R16", (48, 40, 24, 20), None),
+    ("c4_48x48x48x48x48_f32_R64", (48, 12, 10, 8, 6), None),
+    ("c5_16384x2048x64_f64_R4", (2048, 256, 16), None),
+    ("c5_16384x2048x64_f64_R8", (2048, 256, 16), None),
+    ("c5_16384x2048x64_f64_R128", (1024, 64, 16), None),
+    ("paperA_401x201x12x501_f64_R32", (101, 51, 12, 26), None),
+    ("paperB_129x129x129x12x39_f64_R32", (33, 17, 9, 12, 5), None),
+]
+
+
+@pytest.mark.parametrize("name,dims,_", SCALED)
+def test_scaled_configs(mt, oracle, name, dims, _):
+    w = inputs.scaled(inputs.WORKLOADS[name], dims)
+    X = inputs.make_tensor(w)
+    A = inputs.make_factors(w)
+    for k in range(w.ndim):
+        print("case %s dims=%s k=%d" % (name, dims, k), flush=True)
+        got = gpu_mttkrp(mt, X, w.dims, A, k)
+        ref = oracle_mttkrp(oracle, X, w.dims, A, k)
+        err = oracle.normwise_rel_err(got, ref)
+        assert err <= TOL[w.torch_dtype], (name, k, err)
+
+
+# ---------------------------------------------------------------- semantics of the boundary
+def test_M_is_overwritten_and_Ak_never_read(mt, oracle):
+    dims, R = (70, 20, 9), 12
+    X, A = make_problem(dims, R, torch.float64, seed=21)
+    for k in range(3):
+        ref = oracle_mttkrp(oracle, X, dims, A, k)
+        M = torch.full((dims[k], R), float("nan"), dtype=torch.float64, device="cuda")
+        A_nan = list(A)
+        A_nan[k] = torch.full_like(A[k], float("nan"))
+        got = gpu_mttkrp(mt, X, dims, A_nan, k, M=M)
+        assert oracle.normwise_rel_err(got, ref) <= 1e-12
+        A_none = list(A)
+        A_none[k] = None
+        got2 = gpu_mttkrp(mt, X, dims, A_none, k)
+        assert np.array_equal(got, got2)
+
+
+def test_rerun_is_bit_identical_and_ws_variant_matches(mt, oracle):
+    dims, R = (192, 40, 30), 32
+    X, A = make_problem(dims, R, torch.float64, seed=22)
+    for k in range(3):
+        a = gpu_mttkrp(mt, X, dims, A, k)
+        b = gpu_mttkrp(mt, X, dims, A, k)
+        assert np.array_equal(a, b)
+        nbytes = mt.mttkrp_dense_workspace_bytes(dims, R, k, 8)
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        c = gpu_mttkrp(mt, X, dims, A, k, workspace=ws)
+        assert np.array_equal(a, c)
+
+
+def test_errors_enqueue_nothing(mt):
+    import ctypes
+    L = mt.lib()
+    dims, R = (8, 6, 4), 3
+    X, A = make_problem(dims, R, torch.float64, seed=23)
+    Xd = X.cuda()
+    Ad = [a.cuda() for a in A]
+    M = torch.full((8, R), 5.0, dtype=torch.float64, device="cuda")
+    d3 = (ctypes.c_int64 * 3)(*dims)
+    ptrs = (ctypes.c_void_p * 3)(*[a.data_ptr() for a in Ad])
+    bad_dims = (ctypes.c_int64 * 3)(8, 0, 4)
+    no_f1 = (ctypes.c_void_p * 3)(Ad[0].data_ptr(), None, Ad[2].data_ptr())
+    cases = [
+        (3, d3, Xd.data_ptr(), ptrs, R, 3, M.data_ptr(), mt.MTTKRP_ERR_INVALID_ARG),
+        (3, d3, Xd.data_ptr(), ptrs, R, -1, M.data_ptr(), mt.MTTKRP_ERR_INVALID_ARG),
+        (3, d3, Xd.data_ptr(), ptrs, 0, 0, M.data_ptr(), mt.MTTKRP_ERR_INVALID_ARG),
+        (3, bad_dims, Xd.data_ptr(), ptrs, R, 0, M.data_ptr(), mt.MTTKRP_ERR_INVALID_ARG),
+        (1, d3, Xd.data_ptr(), ptrs, R, 0, M.data_ptr(), mt.MTTKRP_ERR_INVALID_ARG),
+        (3, d3, None, ptrs, R, 0, M.data_ptr(), mt.MTTKRP_ERR_INVALID_ARG),
+        (3, d3, Xd.data_ptr(), ptrs, R, 0, None, mt.MTTKRP_ERR_INVALID_ARG),
+        (3, d3, Xd.data_ptr(), no_f1, R, 0, M.data_ptr(), mt.MTTKRP_ERR_INVALID_ARG),
+    ]
+    for (nd, dd, xp, fp, r, k, mp, want) in cases:
+        rc = L.mttkrp_dense_f64(nd, dd, xp, fp, r, k, mp, None)
+        assert rc == want, (nd, r, k, rc)
+    d9 = (ctypes.c_int64 * 9)(*([2] * 9))
+    p9 = (ctypes.c_void_p * 9)(*([Ad[0].data_ptr()] * 9))
+    assert L.mttkrp_dense_f64(9, d9, Xd.data_ptr(), p9, R, 0, M.data_ptr(), None) \
+        == mt.MTTKRP_ERR_UNSUPPORTED
+    # caller-owned workspace too small / misaligned
+    big = (512, 64, 32)
+    nbytes = mt.mttkrp_dense_workspace_bytes(big, 16, 0, 8)
+    assert nbytes > 0
+    Xb, Ab = make_problem(big, 16, torch.float64, seed=24)
+    Xbd = Xb.cuda()
+    Abd = [a.cuda() for a in Ab]
+    Mb = torch.full((512, 16), 5.0, dtype=torch.float64, device="cuda")
+    with pytest.raises(mt.MttkrpError) as e:
+        mt.mttkrp_dense(Xbd, big, Abd, 0, M=Mb,
+                        workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == mt.MTTKRP_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert float(M.min()) == 5.0 and float(M.max()) == 5.0
+    assert float(Mb.min()) == 5.0 and float(Mb.max()) == 5.0
+
+
+# ---------------------------------------------------------------- schedule invariance
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+def test_result_does_not_depend_on_the_decomposition(mt, oracle, dtype):
+    """Tile sizes, split counts and block order are re-schedulings of one sum
+    (Sec. III-D: N_T only changes the schedule), so every setting must agree
+    with the oracle within the tolerance."""
+    dims, R = (200, 36, 14, 5), 24
+    X, A = make_problem(dims, R, dtype, seed=31)
+    refs = [oracle_mttkrp(oracle, X, dims, A, k) for k in range(4)]
+    settings = [
+        {"row_blocks": 1}, {"row_blocks": 2}, {"row_blocks": 3}, {"row_blocks": 4},
+        {"target_items": 1}, {"target_items": 64}, {"target_items": 100000},
+        {"max_steps": 8}, {"xcd_remap": 2}, {"ws_percent": 100, "target_items": 50000},
+    ]
+    try:
+        for st in settings:
+            for key, val in st.items():
+                mt.mttkrp_tune_set(key, val)
+            for k in range(4):
+                print("setting %s k=%d %s" % (st, k, mt.mttkrp_plan_describe(
+                    dims, R, k, 8 if dtype == torch.float64 else 4)), flush=True)
+                got = gpu_mttkrp(mt, X, dims, A, k)
+                assert oracle.normwise_rel_err(got, refs[k]) <= TOL[dtype], (st, k)
+            for key in st:
+                mt.mttkrp_tune_set(key, 0)
+    finally:
+        for key in ("row_blocks", "target_items", "max_steps", "xcd_remap", "ws_percent"):
+            mt.mttkrp_tune_set(key, 0)
+
+
+def test_non_default_stream(mt, oracle):
+    dims, R = (130, 50, 20), 16
+    X, A = make_problem(dims, R, torch.float64, seed=41)
+    ref = oracle_mttkrp(oracle, X, dims, A, 1)
+    st = torch.cuda.Stream()
+    Xd = X.cuda()
+    Ad = [a.cuda() for a in A]
+    torch.cuda.synchronize()
+    with torch.cuda.stream(st):
+        M = mt.mttkrp_dense(Xd, dims, Ad, 1)
+    st.synchronize()
+    assert oracle.normwise_rel_err(M.cpu().numpy(), ref) <= 1e-12
