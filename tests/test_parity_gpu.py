@@ -201,14 +201,14 @@ def test_errors_enqueue_nothing(mt):
         == mt.MTTKRP_ERR_UNSUPPORTED
     # caller-owned workspace too small / misaligned
     big = (512, 64, 32)
-    nbytes = mt.mttkrp_dense_workspace_bytes(big, 16, 0, 8)
+    nbytes = mt.mttkrp_dense_workspace_bytes(big, 16, 1, 8)
     assert nbytes > 0
     Xb, Ab = make_problem(big, 16, torch.float64, seed=24)
     Xbd = Xb.cuda()
     Abd = [a.cuda() for a in Ab]
-    Mb = torch.full((512, 16), 5.0, dtype=torch.float64, device="cuda")
+    Mb = torch.full((64, 16), 5.0, dtype=torch.float64, device="cuda")
     with pytest.raises(mt.MttkrpError) as e:
-        mt.mttkrp_dense(Xbd, big, Abd, 0, M=Mb,
+        mt.mttkrp_dense(Xbd, big, Abd, 1, M=Mb,
                         workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
     assert e.value.status == mt.MTTKRP_ERR_WORKSPACE
     torch.cuda.synchronize()
