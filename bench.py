@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the matrix-free dense MTTKRP on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+One "step" is one pass of the whole hot path over the workload: one MTTKRP
+call per mode (k = 0..d-1) on the same resident tensor, i.e. d streaming
+passes over X.  The default workload is benchmark configuration 2
+(1024 x 1024 x 512 fp64, R = 32, 4 GiB), the one the target (>= 70 % of HBM
+bandwidth for R <= 32) is quoted on.  Inputs are seeded synthetic data already
+resident in HBM when the timed region starts.
+
+Prints ONE JSON line.  ``value`` is GB/s of X streamed over the whole step
+(d * N * s_f / t_step, wall clock between device synchronisations).
+``roofline`` is for the streaming kernel: algorithmic bytes per launch,
+s_f (N + R sum_n I_n) (the paper's infinite-cache model m_inf, Sec. IV-B),
+divided by the mean launch duration measured with HIP events recorded by the
+library on the launch stream around each streaming-kernel launch of the timed
+region.  ``cpu_baseline`` times the CPU oracle (long-double accumulation, as
+used for parity) on a bounded slab of the same tensor on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published
+FP_PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3}   # dense MFMA = vector peak for these types
+
+
+def cpu_baseline(w, X, A, budget_s=15.0):
+    """Time the oracle on the slab X[..., :s] of the workload (all modes).
+
+    The slab is the first s entries of the slowest mode, which is a contiguous
+    prefix of X, so it is the same tensor with a shorter last mode; oracle work
+    is linear in s.  s is chosen from a short calibration run so that the timed
+    part takes about ``budget_s`` seconds.
+    """
+    import numpy as np
+    from oracle import mttkrp_oracle as orc
+    from paper_2510_14891_amd import inputs
+    orc.build()
+    cores = orc.max_threads()
+    lead = w.numel // w.dims[-1]
+
+    def run(s):
+        dims = tuple(w.dims[:-1]) + (s,)
+        Xs = inputs.as_ndarray_view(X[: lead * s].cpu(), dims)
+        As = [a.cpu().numpy() for a in A]
+        As[-1] = As[-1][:s]
+        t0 = time.perf_counter()
+        for k in range(w.ndim):
+            orc.mttkrp(Xs, As, k)
+        return time.perf_counter() - t0
+
+    s0 = max(1, min(w.dims[-1], (1 << 22) // max(lead, 1)))
+    t_cal = run(s0)
+    s = int(max(s0, min(w.dims[-1], s0 * budget_s / max(t_cal, 1e-3))))
+    t = run(s) if s > s0 else t_cal
+    x_bytes = w.ndim * lead * s * w.itemsize
+    return {
+        "value": x_bytes / t / 1e9,
+        "unit": "GB/s of X streamed",
+        "cores": cores,
+        "kind": "oracle",
+        "accumulator": "long double",
+        "seconds": round(t, 3),
+        "gflops_paper": w.ndim * (lead * s) * w.R * w.ndim / t / 1e9,
+        "sample": "slab X[..., :%d] of the last mode (%d of %d entries, %.1f %% of the tensor), "
+                  "all %d modes, one run" % (s, lead * s, w.numel, 100.0 * s / w.dims[-1], w.ndim),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2_1024x1024x512_f64_R32")
+    ap.add_argument("--cpu-budget", type=float, default=15.0,
+                    help="seconds of oracle time for the CPU baseline (0 = skip)")
+    ap.add_argument("--copy-only", action="store_true",
+                    help="run only K plain device copies of the X buffer (the known-size "
+                         "kernel the rocprofv3 FETCH_SIZE/WRITE_SIZE counters are scaled by)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path is one GPU's share at its "
+              "real shape; see DESIGN.md for how it would shard). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2510_14891_amd import binding as mt, inputs, perf_model
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    mt.lib()   # fails loudly when the HIP library is missing
+    w = inputs.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    X = inputs.make_tensor(w, device=dev)
+    A = inputs.make_factors(w, device=dev)
+    M = [torch.empty((I, w.R), dtype=w.torch_dtype, device=dev) for I in w.dims]
+    torch.cuda.synchronize()
+    if args.copy_only:
+        Y = torch.empty_like(X)
+        for _ in range(args.steps):
+            Y.copy_(X)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_only": True, "bytes_read_per_copy": w.numel * w.itemsize,
+                          "bytes_written_per_copy": w.numel * w.itemsize, "copies": args.steps}))
+        return 0
+
+    def step():
+        for k in range(w.ndim):
+            mt.mttkrp_dense(X, w.dims, A, k, M=M[k])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps, wall clock between synchronisations.  The
+    # library records HIP events on the launch stream around every kernel of
+    # these K steps; they are read back after the region has ended.
+    mt.mttkrp_timing_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t_wall = time.perf_counter() - t0
+    ms_per_step = 1e3 * t_wall / args.steps
+    mt.mttkrp_timing_enable(False)
+
+    n_calls = mt.mttkrp_timing_count()
+    first = max(0, n_calls - 512)           # the library keeps the last 512 timed calls
+    s_ms = [[] for _ in range(w.ndim)]
+    c_ms = [[] for _ in range(w.ndim)]
+    for i in range(first, n_calls):
+        a, b = mt.mttkrp_timing_get(i)
+        s_ms[i % w.ndim].append(a)
+        c_ms[i % w.ndim].append(b)
+    per_mode = []
+    stream_ms_all = []
+    for k in range(w.ndim):
+        stream_ms_all += s_ms[k]
+        sm = sum(s_ms[k]) / len(s_ms[k])
+        cm = sum(c_ms[k]) / len(c_ms[k])
+        per_mode.append({
+            "mode": k + 1,
+            "stream_kernel_ms": round(sm, 4),
+            "stream_kernel_ms_min": round(min(s_ms[k]), 4),
+            "combine_kernel_ms": round(cm, 4),
+            "GBps_X": round(w.numel * w.itemsize / (sm + cm) / 1e6, 1),
+            "pct_hbm": round(100 * w.numel * w.itemsize / (sm + cm) / 1e6 / HBM_PEAK_GBPS, 1),
+            "gflops_exec_2NR": round(2 * w.numel * w.R / (sm + cm) / 1e6, 1),
+            "pct_fp_peak": round(100 * 2 * w.numel * w.R / (sm + cm) / 1e9
+                                 / FP_PEAK_TFLOPS[w.dtype], 1),
+            "gflops_paper_NRd": round(w.numel * w.R * w.ndim / (sm + cm) / 1e6, 1),
+            "plan": mt.mttkrp_plan_describe(w.dims, w.R, k, w.itemsize),
+        })
+    kernel_ms = sum(stream_ms_all) / len(stream_ms_all)
+
+    alg_bytes = perf_model.m_inf(w.dims, w.R, w.itemsize)   # per launch
+    exec_flops = 2.0 * w.numel * w.R
+    mem_bound = exec_flops / (FP_PEAK_TFLOPS[w.dtype] * 1e12) <= alg_bytes / (HBM_PEAK_GBPS * 1e9)
+    if mem_bound:
+        achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4)}
+    else:
+        achieved = exec_flops / (kernel_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2),
+                    "peak": FP_PEAK_TFLOPS[w.dtype], "unit": "TFLOP/s",
+                    "frac": round(achieved / FP_PEAK_TFLOPS[w.dtype], 4)}
+    roofline["kernel"] = "mttkrp_stream_kernel"
+    roofline["kernel_ms_mean"] = round(kernel_ms, 4)
+    roofline["launches_timed"] = len(stream_ms_all)
+    roofline["algorithmic_bytes_per_launch"] = alg_bytes
+    roofline["traffic"] = perf_model.measured_traffic(w.name)
+
+    x_gbps = w.ndim * w.numel * w.itemsize / (ms_per_step * 1e-3) / 1e9
+    out = {
+        "metric": "dense MTTKRP GB/s of X streamed (all modes), with GFLOP/s and % of "
+                  "HBM/FP roofline per mode",
+        "value": round(x_gbps, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "dims": list(w.dims), "R": w.R,
+                   "modes_per_step": w.ndim, "x_bytes": w.numel * w.itemsize},
+        "pct_hbm_peak": round(100 * x_gbps / HBM_PEAK_GBPS, 1),
+        "gflops_exec_2NR": round(w.ndim * exec_flops / (ms_per_step * 1e-3) / 1e9, 1),
+        "gflops_paper_NRd": round(w.ndim * w.numel * w.R * w.ndim / (ms_per_step * 1e-3) / 1e9, 1),
+        "per_mode": per_mode,
+        "roofline": roofline,
+    }
+    if args.cpu_budget > 0:
+        out["cpu_baseline"] = cpu_baseline(w, X, A, args.cpu_budget)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -111,14 +111,22 @@ int mttkrp_version(void);
 void mttkrp_release(void);
 
 /*
- * Measurement hooks (Sec. IV-B reports time per MTTKRP).  With timing enabled
- * every core / *_ws call records HIP events on its stream around its streaming
- * kernel and around its combine kernel.  mttkrp_timing_last waits for those
- * events and returns the two durations in milliseconds of the most recent
- * call on the current device (combine_ms = 0 when no combine kernel ran).
- * Returns MTTKRP_ERR_INVALID_ARG if nothing was recorded.
+ * Measurement hooks (Sec. IV-B reports time per MTTKRP).  While timing is
+ * enabled every core / *_ws call records HIP events on its own stream around
+ * its streaming kernel and around its combine kernel.  Enabling (re)starts the
+ * count of timed calls on every device; the most recent 512 timed calls of a
+ * device are kept.
+ *   mttkrp_timing_count  timed calls on the current device since enabling
+ *   mttkrp_timing_get    waits for the events of timed call `index`
+ *                        (0-based, in call order) and returns the two kernel
+ *                        durations in milliseconds (combine_ms = 0 when no
+ *                        combine kernel ran); MTTKRP_ERR_INVALID_ARG when the
+ *                        index was never recorded or has been overwritten
+ *   mttkrp_timing_last   the same for the most recent timed call
  */
 int mttkrp_timing_enable(int enable);
+int64_t mttkrp_timing_count(void);
+int mttkrp_timing_get(int64_t index, float* stream_ms, float* combine_ms);
 int mttkrp_timing_last(float* stream_ms, float* combine_ms);
 
 /*

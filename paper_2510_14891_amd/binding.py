@@ -27,7 +27,8 @@ EXPORTED = (
     "mttkrp_dense_f64", "mttkrp_dense_f32", "mttkrp_dense_workspace_bytes",
     "mttkrp_dense_f64_ws", "mttkrp_dense_f32_ws", "mttkrp_status_string",
     "mttkrp_version", "mttkrp_release", "mttkrp_timing_enable",
-    "mttkrp_timing_last", "mttkrp_tune_set", "mttkrp_plan_describe",
+    "mttkrp_timing_count", "mttkrp_timing_get", "mttkrp_timing_last",
+    "mttkrp_tune_set", "mttkrp_plan_describe",
 )
 
 _lib = None
@@ -72,6 +73,10 @@ def lib() -> ctypes.CDLL:
     L.mttkrp_timing_last.restype = ctypes.c_int
     L.mttkrp_timing_last.argtypes = [ctypes.POINTER(ctypes.c_float),
                                      ctypes.POINTER(ctypes.c_float)]
+    L.mttkrp_timing_count.restype = ctypes.c_int64
+    L.mttkrp_timing_get.restype = ctypes.c_int
+    L.mttkrp_timing_get.argtypes = [ctypes.c_int64, ctypes.POINTER(ctypes.c_float),
+                                    ctypes.POINTER(ctypes.c_float)]
     L.mttkrp_tune_set.restype = ctypes.c_int
     L.mttkrp_tune_set.argtypes = [ctypes.c_char_p, ctypes.c_int64]
     L.mttkrp_plan_describe.restype = ctypes.c_int
@@ -106,6 +111,17 @@ def mttkrp_timing_last():
     """(stream_ms, combine_ms) of the most recent call on the current device."""
     a, b = ctypes.c_float(0), ctypes.c_float(0)
     _check(lib().mttkrp_timing_last(ctypes.byref(a), ctypes.byref(b)))
+    return float(a.value), float(b.value)
+
+
+def mttkrp_timing_count() -> int:
+    return int(lib().mttkrp_timing_count())
+
+
+def mttkrp_timing_get(index: int):
+    """(stream_ms, combine_ms) of timed call ``index`` on the current device."""
+    a, b = ctypes.c_float(0), ctypes.c_float(0)
+    _check(lib().mttkrp_timing_get(int(index), ctypes.byref(a), ctypes.byref(b)))
     return float(a.value), float(b.value)
 
 

@@ -29,6 +29,7 @@
 #include <string.h>
 
 #include <mutex>
+#include <new>
 
 #include "../../include/mttkrp.h"
 
@@ -580,13 +581,18 @@ void launch_stream_rb(int RB, int JB, const StreamArgs<T>& a, dim3 grid, hipStre
     }
 }
 
+constexpr int kTimingSlots = 512;   // ring of timed calls kept per device
+
+struct TimedCall {
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};   // stream begin/end, combine begin/end
+    bool combine = false;
+};
+
 struct DeviceState {
     void* ws = nullptr;
     size_t ws_bytes = 0;
-    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
-    bool have_events = false;
-    bool timed = false;          // ev[] hold a recorded call
-    bool timed_combine = false;
+    TimedCall* calls = nullptr;  // kTimingSlots entries once timing has been used
+    int64_t n_timed = 0;         // calls recorded since timing was last enabled
 };
 DeviceState g_dev[kMaxDevices];
 bool g_timing = false;
@@ -640,11 +646,21 @@ int run(int ndim, const int64_t* dims, const T* X, const T* const* factors, int 
         }
     }
     const bool timing = g_timing;
-    if (timing && !ds.have_events) {
-        for (int e = 0; e < 4; ++e)
-            if (hipEventCreate(&ds.ev[e]) != hipSuccess)
+    TimedCall* tc = nullptr;
+    if (timing) {
+        if (!ds.calls) {
+            TimedCall* calls = new (std::nothrow) TimedCall[kTimingSlots];
+            if (!calls)
                 return MTTKRP_ERR_DEVICE;
-        ds.have_events = true;
+            for (int c = 0; c < kTimingSlots; ++c)
+                for (int e = 0; e < 4; ++e)
+                    if (hipEventCreate(&calls[c].ev[e]) != hipSuccess) {
+                        delete[] calls;   // events created so far are leaked; creation does not fail in practice
+                        return MTTKRP_ERR_DEVICE;
+                    }
+            ds.calls = calls;
+        }
+        tc = &ds.calls[ds.n_timed % kTimingSlots];
     }
 
     StreamArgs<T> a;
@@ -690,30 +706,32 @@ int run(int ndim, const int64_t* dims, const T* X, const T* const* factors, int 
 
     (void)hipGetLastError();
     if (timing)
-        (void)hipEventRecord(ds.ev[0], st);
+        (void)hipEventRecord(tc->ev[0], st);
     launch_stream_rb<T>(pl.RB, pl.JB, a, dim3((unsigned)blocks), st);
-    if (timing)
-        (void)hipEventRecord(ds.ev[1], st);
+    if (timing) {
+        (void)hipEventRecord(tc->ev[1], st);
+        tc->combine = false;
+    }
     if (hipGetLastError() != hipSuccess)
         return MTTKRP_ERR_DEVICE;
-    ds.timed_combine = false;
     if (pl.n_slots > 1) {
         const int64_t n_elems = pl.dims[k] * (int64_t)R;
         const int64_t stride_row = k == 0 ? R : pl.n_slots * (int64_t)R;
         const int64_t stride_slot = k == 0 ? pl.dims[0] * (int64_t)R : R;
         if (timing)
-            (void)hipEventRecord(ds.ev[2], st);
+            (void)hipEventRecord(tc->ev[2], st);
         hipLaunchKernelGGL((mttkrp_combine_kernel<T>), dim3((unsigned)ceil_div(n_elems, 256)),
                            dim3(256), 0, st, (const T*)ws, M, n_elems, R, (int)pl.n_slots,
                            stride_row, stride_slot);
         if (timing) {
-            (void)hipEventRecord(ds.ev[3], st);
-            ds.timed_combine = true;
+            (void)hipEventRecord(tc->ev[3], st);
+            tc->combine = true;
         }
         if (hipGetLastError() != hipSuccess)
             return MTTKRP_ERR_DEVICE;
     }
-    ds.timed = timing;
+    if (timing)
+        ds.n_timed += 1;
     return MTTKRP_OK;
 }
 
@@ -777,7 +795,7 @@ void mttkrp_release(void)
         return;
     for (int d = 0; d < kMaxDevices; ++d) {
         DeviceState& ds = g_dev[d];
-        if (!ds.ws && !ds.have_events)
+        if (!ds.ws && !ds.calls)
             continue;
         if (hipSetDevice(d) != hipSuccess)
             continue;
@@ -786,11 +804,14 @@ void mttkrp_release(void)
             (void)hipFree(ds.ws);
         ds.ws = nullptr;
         ds.ws_bytes = 0;
-        if (ds.have_events)
-            for (int e = 0; e < 4; ++e)
-                (void)hipEventDestroy(ds.ev[e]);
-        ds.have_events = false;
-        ds.timed = false;
+        if (ds.calls) {
+            for (int c = 0; c < kTimingSlots; ++c)
+                for (int e = 0; e < 4; ++e)
+                    (void)hipEventDestroy(ds.calls[c].ev[e]);
+            delete[] ds.calls;
+        }
+        ds.calls = nullptr;
+        ds.n_timed = 0;
     }
     (void)hipSetDevice(cur);
 }
@@ -799,10 +820,22 @@ int mttkrp_timing_enable(int enable)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     g_timing = enable != 0;
+    if (g_timing)
+        for (int d = 0; d < kMaxDevices; ++d)
+            g_dev[d].n_timed = 0;
     return MTTKRP_OK;
 }
 
-int mttkrp_timing_last(float* stream_ms, float* combine_ms)
+int64_t mttkrp_timing_count(void)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return 0;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    return g_dev[dev].n_timed;
+}
+
+int mttkrp_timing_get(int64_t index, float* stream_ms, float* combine_ms)
 {
     if (!stream_ms || !combine_ms)
         return MTTKRP_ERR_INVALID_ARG;
@@ -813,16 +846,22 @@ int mttkrp_timing_last(float* stream_ms, float* combine_ms)
         return MTTKRP_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(g_mutex);
     DeviceState& ds = g_dev[dev];
-    if (!ds.timed)
+    if (!ds.calls || index < 0 || index >= ds.n_timed || index < ds.n_timed - kTimingSlots)
         return MTTKRP_ERR_INVALID_ARG;
+    TimedCall& tc = ds.calls[index % kTimingSlots];
     *combine_ms = 0.0f;
-    if (hipEventSynchronize(ds.timed_combine ? ds.ev[3] : ds.ev[1]) != hipSuccess)
+    if (hipEventSynchronize(tc.combine ? tc.ev[3] : tc.ev[1]) != hipSuccess)
         return MTTKRP_ERR_DEVICE;
-    if (hipEventElapsedTime(stream_ms, ds.ev[0], ds.ev[1]) != hipSuccess)
+    if (hipEventElapsedTime(stream_ms, tc.ev[0], tc.ev[1]) != hipSuccess)
         return MTTKRP_ERR_DEVICE;
-    if (ds.timed_combine && hipEventElapsedTime(combine_ms, ds.ev[2], ds.ev[3]) != hipSuccess)
+    if (tc.combine && hipEventElapsedTime(combine_ms, tc.ev[2], tc.ev[3]) != hipSuccess)
         return MTTKRP_ERR_DEVICE;
     return MTTKRP_OK;
+}
+
+int mttkrp_timing_last(float* stream_ms, float* combine_ms)
+{
+    return mttkrp_timing_get(mttkrp_timing_count() - 1, stream_ms, combine_ms);
 }
 
 int mttkrp_tune_set(const char* key, int64_t value)
