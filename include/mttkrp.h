@@ -136,7 +136,7 @@ int mttkrp_timing_last(float* stream_ms, float* combine_ms);
  *   "row_blocks"    16-row MFMA blocks per wavefront (1..4)
  *   "target_items"  wavefront work items the planner aims for
  *   "max_steps"     upper bound on 4-column steps per work item
- *   "xcd_remap"     1 = contiguous item ranges per XCD, 2 = plain order
+ *   "xcd_remap"     1 = contiguous item ranges per XCD, 2 = plain order (default)
  *   "ws_percent"    cap on first-mode partial-sum traffic, percent of X bytes
  * Returns MTTKRP_ERR_INVALID_ARG for an unknown key or a value out of range.
  */

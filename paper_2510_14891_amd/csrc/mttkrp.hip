@@ -39,6 +39,12 @@ constexpr int kMaxOuter = MTTKRP_MAX_NDIM - 2;
 constexpr int kWaves = 4;           // independent wavefronts per workgroup
 constexpr int kBlockThreads = 64 * kWaves;
 constexpr int kMaxDevices = 16;
+#ifndef MTTKRP_MIN_BLOCKS
+#define MTTKRP_MIN_BLOCKS 2
+#endif
+#ifndef MTTKRP_DEPTH
+#define MTTKRP_DEPTH 4
+#endif
 
 typedef double double4_t __attribute__((ext_vector_type(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
@@ -81,9 +87,11 @@ template <typename T> struct StreamArgs {
     int32_t cols_per_isplit;     // inner columns per inner split (multiple of 4)
     int32_t n_items;
     int32_t n_slots;             // partial slots per output row (k != 0)
+    int32_t n_splits;            // column-space splits (outer splits x inner splits)
     int32_t xcd_remap;
     int32_t no_inner;            // 1: no column mode at all; A_in is only a readable dummy
 };
+
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ int64_t uni64(int64_t v)
@@ -99,8 +107,8 @@ __device__ __forceinline__ int64_t uni64(int64_t v)
 // Outer column modes: the first one ("mid") is walked by a plain counter; the
 // others ("far") only change when mid wraps, and are then re-derived from the
 // linear outer index by division (rare).
-template <typename T, int RB, int JB>
-__global__ void __launch_bounds__(kBlockThreads, 2)
+template <typename T, int RB, int JB, int U>
+__global__ void __launch_bounds__(kBlockThreads, MTTKRP_MIN_BLOCKS)
 mttkrp_stream_kernel(const StreamArgs<T> p)
 {
     typedef Mfma<T> MF;
@@ -111,14 +119,21 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
     uint32_t blk = blockIdx.x;
     if (p.xcd_remap)   // workgroups go round-robin over the 8 XCDs: give each XCD a contiguous range
         blk = (blk & 7u) * (gridDim.x >> 3) + (blk >> 3);
-    uint32_t it = blk * kWaves + wave;
-    if (it >= (uint32_t)p.n_items)
+    // Item decode.  First mode: the four wavefronts of a workgroup share (row
+    // block, column chunk) and take four consecutive column-space splits, so that
+    // their tiles can be summed in LDS; a whole workgroup is in range or not.
+    // Other modes: one independent item per wavefront.
+    uint32_t it = p.first_mode ? blk : blk * kWaves + wave;
+    if (it >= (uint32_t)(p.first_mode ? p.n_items / kWaves : p.n_items))
         return;
     const int rowblk = uni((int)(it % (uint32_t)p.n_rowblk));  it /= (uint32_t)p.n_rowblk;
     const int jchunk = uni((int)(it % (uint32_t)p.n_jchunk));  it /= (uint32_t)p.n_jchunk;
     const int batch = uni((int)(it % (uint32_t)p.n_batch));    it /= (uint32_t)p.n_batch;
-    const int isp = uni((int)(it % (uint32_t)p.n_isplit));     it /= (uint32_t)p.n_isplit;
-    const int osp = uni((int)it);
+    const int group = uni((int)it);                             // first mode: split group
+    const uint32_t sp = p.first_mode ? it * kWaves + wave : it; // column-space split
+    const bool empty = sp >= (uint32_t)p.n_splits;              // padding of the last split group
+    const int osp = empty ? 0 : uni((int)(sp / (uint32_t)p.n_isplit));
+    const int isp = empty ? 0 : uni((int)(sp - (uint32_t)osp * (uint32_t)p.n_isplit));
 
     const int il = lane & 15;   // row inside a 16-row block (operand A) = column inside a 16-column block (B, D)
     const int kk = lane >> 4;   // which of the step's four columns this lane feeds
@@ -145,15 +160,23 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
     const int ia_end = min(p.I_in, ia_begin + p.cols_per_isplit);
     const int steps_in = (ia_end - ia_begin + 3) >> 2;
     const int64_t o_begin = (int64_t)osp * p.o_per_item;
-    const int o_count = uni((int)min(p.o_per_item, p.o_total - o_begin));
+    const int o_count = empty ? 0 : uni((int)min(p.o_per_item, p.o_total - o_begin));
 
     const T* const xlane = p.X + (int64_t)batch * p.sx_batch + (row_base + il_c);
     const int64_t x_step = 4 * p.sx_in;
     const bool no_inner = p.no_inner != 0;   // then A_in is a readable dummy and b = 1
     const int dim_mid = p.dim_out[0];        // 1 when there is no outer mode
     const int64_t sx_mid = p.sx_out[0];
-    const T* const A_mid = p.n_out > 0 ? p.A_out[0] : p.A_in;   // dummy when unused
     const bool has_mid = p.n_out > 0;
+    const T* const A_mid = has_mid ? p.A_out[0] : p.A_in;   // dummy when unused
+
+    // Last step of a sweep: lanes whose column lies beyond the inner range read
+    // the sweep's last column instead and get weight 0.  How many lanes that is
+    // depends only on the item, not on the step.
+    const int over = max(kk - ((ia_end - ia_begin - 1) & 3), 0);
+    const bool lane_ok = over == 0;
+    const int64_t x_back = (int64_t)over * p.sx_in;
+    const int64_t b_back = (int64_t)over * R;   // bbase is per-lane in the last step only
 
     // State of the outer walk (all wave-uniform except the factor values).
     int i_mid = 0;
@@ -161,14 +184,7 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
     int64_t xoff_far = 0;         // X offset of the far modes
     T Qfar[JB];                   // product of the far modes' factor entries
     T Q[JB];                      // ... times the mid mode's entry: weight of the sweep being issued
-    T mid_next[JB];               // mid factor entries of row i_mid + 1, loaded one sweep ahead
-    auto load_mid = [&](int i, T (&dst)[JB]) {
-        const T* a = A_mid + (int64_t)(has_mid ? i : 0) * R;
-#pragma unroll
-        for (int jb = 0; jb < JB; ++jb)
-            dst[jb] = a[jc[jb]];
-    };
-    auto load_far = [&]() {       // Qfar and Q from the current indices (rare; waits for its loads)
+    auto load_far = [&]() {       // Qfar from the current far indices (rare)
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
             Qfar[jb] = (T)1;
@@ -181,13 +197,17 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
                     Qfar[jb] *= a[jc[jb]];
             }
         }
-        T mid_now[JB];
-        load_mid(i_mid, mid_now);
+    };
+    auto load_Q = [&]() {         // Q of the sweep the cursor enters
+        const T* a = A_mid + (int64_t)(has_mid ? i_mid : 0) * R;
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
-            Q[jb] = has_mid ? Qfar[jb] * mid_now[jb] : Qfar[jb];
+            Q[jb] = has_mid ? Qfar[jb] * a[jc[jb]] : Qfar[jb];
     };
-    {   // decode the first outer index of this item (the only divisions of the walk)
+#pragma unroll
+    for (int m = 0; m < kMaxOuter; ++m)
+        i_far[m] = 0;
+    if (o_begin > 0) {   // decode the first outer index of this item (the only divisions of the walk)
         int64_t t = uni64(o_begin / dim_mid);
         i_mid = uni((int)(o_begin - t * dim_mid));
 #pragma unroll
@@ -202,73 +222,76 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
         }
     }
     load_far();
-    load_mid(min(i_mid + 1, dim_mid - 1), mid_next);
+    load_Q();
 
-    int ia = ia_begin;
-    int s_in = 0;
+    // Cursor of the issue side: it points at the next step to issue.
+    int s_in = 0;                       // step inside the current sweep
     const T* xp = xlane + xoff_far + (int64_t)i_mid * sx_mid + (int64_t)(ia_begin + kk) * p.sx_in;
+    const T* bbase = p.A_in + (int64_t)ia_begin * R;            // wave-uniform: factor row of the step's first column
+    uint32_t boff[JB];                                          // per-lane byte offset of (column kk, output column j)
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb)
+        boff[jb] = ((uint32_t)kk * (uint32_t)R + (uint32_t)jc[jb]) * (uint32_t)sizeof(T);
+    const int n_steps = o_count * steps_in;   // < 2^30, checked on the host
+    int remaining = n_steps;        // steps not yet issued, the cursor's included
+    bool parked = false;                // all steps issued: the cursor stays on the last one, weight 0
+    // Steps that need no lane masking: all of a sweep when its length is a multiple of four
+    // columns, else all but the last.
+    const int steps_plain = ((ia_end - ia_begin) & 3) == 0 ? steps_in : steps_in - 1;
 
-    // Issue the loads of the step the cursor points at into one operand set.
+    auto next_sweep = [&]() {           // wave-uniform, once per inner sweep
+        s_in = 0;
+        bbase = p.A_in + (int64_t)ia_begin * R;
+        i_mid += 1;
+        if (i_mid >= dim_mid) {         // mid wraps: carry into the far modes
+            i_mid = 0;
+            bool carry = true;
+#pragma unroll
+            for (int m = 1; m < kMaxOuter; ++m) {
+                if (m < p.n_out && carry) {
+                    i_far[m] += 1;
+                    xoff_far += p.sx_out[m];
+                    if (i_far[m] < p.dim_out[m]) {
+                        carry = false;
+                    } else {
+                        xoff_far -= (int64_t)i_far[m] * p.sx_out[m];
+                        i_far[m] = 0;
+                    }
+                }
+            }
+            load_far();
+        }
+        load_Q();
+        xp = xlane + xoff_far + (int64_t)i_mid * sx_mid + (int64_t)(ia_begin + kk) * p.sx_in;
+    };
+    // Generic single step: issue the loads of the cursor's step into one operand set ...
     auto issue = [&](T (&xn)[RB], T (&bn)[JB], T (&qn)[JB]) {
-        // lanes whose column lies beyond the inner range read a valid column instead and get q = 0
-        const int over = max(ia + kk - (ia_end - 1), 0);
-        const T* xe = xp - (int64_t)over * p.sx_in;
-        const int kk_c = kk - over;
+        const bool last = s_in == steps_in - 1;           // wave-uniform
+        const T* xe = last ? xp - x_back : xp;
+        const char* be = (const char*)(last ? bbase - b_back : bbase);
 #pragma unroll
         for (int r = 0; r < RB; ++r)
             xn[r] = __builtin_nontemporal_load(xe + 16 * r);
-        const T* b = p.A_in + (int64_t)(ia + kk_c) * R;
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
-            bn[jb] = b[jc[jb]];
+            bn[jb] = no_inner ? (T)1 : *(const T*)(be + boff[jb]);
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
-            qn[jb] = over == 0 ? Q[jb] : (T)0;
+            qn[jb] = (parked || (last && !lane_ok)) ? (T)0 : Q[jb];
     };
-    // Move the cursor one step on (wave-uniform control flow).  Past the last
-    // step the cursor parks: it keeps pointing at the last step with weight 0,
-    // so that a surplus issue stays in bounds and adds nothing.
-    int steps_left = o_count * steps_in - 1;   // steps after the one the cursor points at
+    // ... and move the cursor one step on.
     auto advance = [&]() {
-        if (steps_left <= 0) {
-#pragma unroll
-            for (int jb = 0; jb < JB; ++jb)
-                Q[jb] = (T)0;
+        remaining -= 1;
+        if (remaining <= 0) {
+            parked = true;
             return;
         }
-        steps_left -= 1;
         s_in += 1;
         if (s_in < steps_in) {
-            ia += 4;
             xp += x_step;
-        } else {                  // next sweep
-            s_in = 0;
-            ia = ia_begin;
-            i_mid += 1;
-            if (i_mid >= dim_mid) {   // mid wraps: carry into the far modes
-                i_mid = 0;
-                bool carry = true;
-#pragma unroll
-                for (int m = 1; m < kMaxOuter; ++m) {
-                    if (m < p.n_out && carry) {
-                        i_far[m] += 1;
-                        xoff_far += p.sx_out[m];
-                        if (i_far[m] < p.dim_out[m]) {
-                            carry = false;
-                        } else {
-                            xoff_far -= (int64_t)i_far[m] * p.sx_out[m];
-                            i_far[m] = 0;
-                        }
-                    }
-                }
-                load_far();
-            } else {
-#pragma unroll
-                for (int jb = 0; jb < JB; ++jb)
-                    Q[jb] = Qfar[jb] * mid_next[jb];
-            }
-            load_mid(min(i_mid + 1, dim_mid - 1), mid_next);
-            xp = xlane + xoff_far + (int64_t)i_mid * sx_mid + (int64_t)(ia_begin + kk) * p.sx_in;
+            bbase += 4 * (int64_t)R;
+        } else {
+            next_sweep();
         }
     };
 
@@ -278,48 +301,121 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
             acc[r][jb] = (acc_t)(0);
-    auto consume = [&](const T (&xc)[RB], const T (&bn)[JB], const T (&qn)[JB]) {
-        T bc[JB];
+
+    // Steps are taken in batches of U: first all loads of the batch are issued
+    // (U steps of X and factor rows in flight per wavefront), then the MFMAs of
+    // the U steps run in issue order, each waiting only for its own operands.
+    // Other wavefronts of the SIMD fill the gaps between batches.
+    //   plain batch:   U unmasked steps of one sweep: one weight Q, constant strides
+    //   generic batch: any steps (sweep boundaries, masked last step, parked padding)
+    for (int done = 0; done < n_steps; done += U) {
+        T xs[U][RB], bs[U][JB], qs[U][JB];
+        if (!parked && remaining >= U && s_in + U <= steps_plain) {
+            const T* xu = xp;
+            const char* bu = (const char*)bbase;
 #pragma unroll
-        for (int jb = 0; jb < JB; ++jb)
-            bc[jb] = (no_inner ? (T)1 : bn[jb]) * qn[jb];
+            for (int u = 0; u < U; ++u) {
 #pragma unroll
-        for (int r = 0; r < RB; ++r)
+                for (int r = 0; r < RB; ++r)
+                    xs[u][r] = __builtin_nontemporal_load(xu + 16 * r);
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb) {
+                    bs[u][jb] = *(const T*)(bu + boff[jb]);
+                    qs[u][jb] = Q[jb];
+                }
+                xu += x_step;
+                bu += 4 * (int64_t)R * (int64_t)sizeof(T);
+            }
+            remaining -= U;
+            if (remaining <= 0) {       // park on the batch's last step
+                parked = true;
+                s_in += U - 1;
+                xp += (U - 1) * x_step;
+                bbase += (U - 1) * 4 * (int64_t)R;
+            } else {
+                s_in += U;
+                xp += U * x_step;
+                bbase += U * 4 * (int64_t)R;
+                if (s_in >= steps_in)
+                    next_sweep();
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                issue(xs[u], bs[u], qs[u]);
+                advance();
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            T bc[JB];
 #pragma unroll
             for (int jb = 0; jb < JB; ++jb)
-                acc[r][jb] = MF::run(xc[r], bc[jb], acc[r][jb]);
-    };
-
-    // Two operand sets in flight, no register copies: while one step's MFMAs
-    // run, the loads of the next step are outstanding.  Steps are taken in
-    // pairs; an odd count is padded by one parked (zero-weight) step.
-    T x0[RB], b0[JB], q0[JB], x1[RB], b1[JB], q1[JB];
-    const int n_pairs = (o_count * steps_in + 1) >> 1;
-    issue(x0, b0, q0);
-    for (int pr = 0; pr < n_pairs; ++pr) {
-        advance();
-        issue(x1, b1, q1);
-        consume(x0, b0, q0);
-        advance();
-        issue(x0, b0, q0);
-        consume(x1, b1, q1);
+                bc[jb] = bs[u][jb] * qs[u][jb];
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb)
+                    acc[r][jb] = MF::run(xs[u][r], bc[jb], acc[r][jb]);
+        }
     }
 
     // Epilogue.
     if (p.first_mode) {
-        const int64_t split = (int64_t)osp * p.n_isplit + isp;
-        T* o = p.out + split * ((int64_t)p.I0 * R);
+        // Sum the four wavefronts' tiles in LDS in a fixed order, (w0 + w2) + (w1 + w3);
+        // all hold the same (row, column) entries in the same registers.
+        extern __shared__ unsigned char lds_raw[];
+        T* lds = reinterpret_cast<T*>(lds_raw);
+        constexpr int kTile = RB * JB * 4 * 64;          // values per wavefront tile
+        if (wave >= 2) {
+            T* dst = lds + (wave - 2) * kTile + lane;
 #pragma unroll
-        for (int r = 0; r < RB; ++r)
+            for (int r = 0; r < RB; ++r)
 #pragma unroll
-            for (int jb = 0; jb < JB; ++jb)
+                for (int jb = 0; jb < JB; ++jb)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int row = row_base + 16 * r + MF::row(lane, q);
-                    const int j = j_first + 16 * jb + il;
-                    if (row >= first_row && row < p.I0 && j < R)
-                        o[(int64_t)row * R + j] = acc[r][jb][q];
-                }
+                    for (int q = 0; q < 4; ++q)
+                        dst[((r * JB + jb) * 4 + q) * 64] = acc[r][jb][q];
+        }
+        __syncthreads();
+        if (wave < 2) {
+            const T* src = lds + wave * kTile + lane;
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        acc[r][jb][q] += src[((r * JB + jb) * 4 + q) * 64];
+        }
+        __syncthreads();
+        if (wave == 1) {
+            T* dst = lds + lane;
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        dst[((r * JB + jb) * 4 + q) * 64] = acc[r][jb][q];
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const T* src = lds + lane;
+            T* o = p.out + (int64_t)group * ((int64_t)p.I0 * R);
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const T v = acc[r][jb][q] + src[((r * JB + jb) * 4 + q) * 64];
+                        const int row = row_base + 16 * r + MF::row(lane, q);
+                        const int j = j_first + 16 * jb + il;
+                        if (row >= first_row && row < p.I0 && j < R)
+                            o[(int64_t)row * R + j] = v;
+                    }
+        }
     } else {
         const int64_t slot = ((int64_t)osp * p.n_isplit + isp) * p.n_rowblk + rowblk;
         T* o = p.out + ((int64_t)batch * p.n_slots + slot) * R;
@@ -401,6 +497,7 @@ struct Plan {
     int64_t o_total = 1, o_per_item = 1, n_osplit = 1;
     int64_t n_items = 0;
     int64_t n_slots = 1;       // partial sums per output entry
+    int64_t n_splits = 1;      // column-space splits
     int64_t steps_per_item = 0;
     size_t ws_bytes = 0;
     bool xcd_remap = true;
@@ -516,47 +613,92 @@ int make_plan(int ndim, const int64_t* dims, int R, int k, int sbytes, Plan& pl)
     if (F < 1)
         F = 1;
     if (k == 0) {
-        // partial tiles are written once and read once: keep that below ws_percent of X
-        const double pct = tn.ws_percent > 0 ? (double)tn.ws_percent : 3.0;
-        const double cap = pct * 0.01 * (double)pl.N / (2.0 * (double)I0 * (double)R);
+        // One partial tile per workgroup (four splits) is written once and read once: keep
+        // that traffic below ws_percent of the bytes of X, or 32 MiB if that is more.
+        const double pct = tn.ws_percent > 0 ? (double)tn.ws_percent : 2.0;
+        double budget = pct * 0.01 * (double)pl.N * sbytes;
+        if (budget < 32.0 * 1048576.0)
+            budget = 32.0 * 1048576.0;
+        const double cap = kWaves * budget / (2.0 * (double)I0 * (double)R * sbytes);
         if ((double)F > cap)
             F = cap < 1.0 ? 1 : (int64_t)cap;
     }
     if (F < ceil_div(steps_all, max_steps))
         F = ceil_div(steps_all, max_steps);
-    pl.n_osplit = F < pl.o_total ? F : pl.o_total;
-    pl.o_per_item = ceil_div(pl.o_total, pl.n_osplit);
-    pl.n_osplit = ceil_div(pl.o_total, pl.o_per_item);
-    int64_t F_in = ceil_div(F, pl.n_osplit);
-    if (pl.o_per_item > 1)
-        F_in = 1;   // inner splitting only once every item is down to one outer iteration
-    if (F_in > steps_in)
-        F_in = steps_in;
-    pl.cols_per_isplit = (int)(4 * ceil_div(steps_in, F_in));
-    pl.n_isplit = (int)ceil_div(pl.I_in, pl.cols_per_isplit);
+    if (F < ceil_div(pl.o_total, (int64_t)1 << 29))
+        F = ceil_div(pl.o_total, (int64_t)1 << 29);
+    // F = outer splits x inner splits.  Among up to eight inner splits (each at least eight
+    // steps long) take the pair whose largest item is closest to the average item.
+    {
+        double best_eff = -1.0;
+        for (int64_t ni = 1; ni <= 8; ++ni) {
+            if (ni > 1 && steps_in / ni < 8)
+                break;
+            int64_t no = F / ni;
+            if (no < 1)
+                no = 1;
+            if (no > pl.o_total)
+                no = pl.o_total;
+            if (ni * pl.o_total < F && ni < 8 && steps_in / (ni + 1) >= 8)
+                continue;     // even every sweep on its own is too few: split the inner mode further
+            const int64_t opi = ceil_div(pl.o_total, no);
+            no = ceil_div(pl.o_total, opi);
+            const int64_t in_steps = ceil_div(steps_in, ni);
+            const int64_t n_in = ceil_div(pl.I_in, 4 * in_steps);
+            const double avg = (double)steps_all / (double)(no * n_in);
+            double eff = avg / (double)(opi * in_steps);
+            const double ratio = (double)(no * n_in) / (double)F;    // stay near the wanted count
+            if (ratio < 0.75)
+                eff *= ratio / 0.75;
+            if (eff > best_eff + 1e-9) {
+                best_eff = eff;
+                pl.n_osplit = no;
+                pl.o_per_item = opi;
+                pl.cols_per_isplit = (int)(4 * in_steps);
+                pl.n_isplit = (int)n_in;
+            }
+        }
+    }
     pl.steps_per_item = pl.o_per_item * (pl.cols_per_isplit / 4);
     if (pl.steps_per_item >= ((int64_t)1 << 30))
         return MTTKRP_ERR_UNSUPPORTED;
-
-    pl.n_items = base_items * pl.n_osplit * pl.n_isplit;
-    if (pl.n_items >= ((int64_t)1 << 31) - 64)
+    pl.n_splits = pl.n_osplit * pl.n_isplit;
+    if (pl.n_splits >= ((int64_t)1 << 30))
         return MTTKRP_ERR_UNSUPPORTED;
-    if (k == 0)
-        pl.n_slots = pl.n_osplit * pl.n_isplit;
-    else
-        pl.n_slots = pl.n_osplit * pl.n_isplit * pl.n_rowblk;
-    if (pl.n_slots >= ((int64_t)1 << 31))
+    if (k == 0) {
+        pl.n_slots = ceil_div(pl.n_splits, kWaves);      // one partial tile per workgroup
+        pl.n_items = base_items * pl.n_slots * kWaves;
+    } else {
+        pl.n_slots = pl.n_splits * pl.n_rowblk;
+        pl.n_items = base_items * pl.n_splits;
+    }
+    if (pl.n_items >= ((int64_t)1 << 31) - 64 || pl.n_slots >= ((int64_t)1 << 31))
         return MTTKRP_ERR_UNSUPPORTED;
     pl.ws_bytes = pl.n_slots > 1
         ? (size_t)pl.n_slots * (size_t)dims[k] * (size_t)R * (size_t)sbytes : 0;
-    pl.xcd_remap = tn.xcd_remap != 2;
+    pl.xcd_remap = tn.xcd_remap == 1;
     return MTTKRP_OK;
+}
+
+// Steps per batch (= steps of loads in flight per wavefront): as many as fit
+// next to the accumulators in about 168 registers (three wavefronts per SIMD),
+// between 2 and MTTKRP_DEPTH.
+template <typename T, int RB, int JB> constexpr int batch_steps()
+{
+    constexpr int w = (int)sizeof(T) / 4;                 // registers per value
+    constexpr int acc = RB * JB * 4 * w;
+    constexpr int per_step = (RB + 2 * JB) * w;
+    constexpr int u = (168 - 44 - acc) / per_step;
+    return u < 2 ? 2 : (u > MTTKRP_DEPTH ? MTTKRP_DEPTH : u);
 }
 
 template <typename T, int RB, int JB>
 void launch_stream(const StreamArgs<T>& a, dim3 grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((mttkrp_stream_kernel<T, RB, JB>), grid, dim3(kBlockThreads), 0, st, a);
+    // first mode: two wavefront tiles of LDS for the cross-wavefront sum
+    const size_t lds = a.first_mode ? (size_t)2 * RB * JB * 4 * 64 * sizeof(T) : 0;
+    hipLaunchKernelGGL((mttkrp_stream_kernel<T, RB, JB, batch_steps<T, RB, JB>()>), grid,
+                       dim3(kBlockThreads), lds, st, a);
 }
 
 template <typename T, int RB>
@@ -696,6 +838,7 @@ int run(int ndim, const int64_t* dims, const T* X, const T* const* factors, int 
     a.cols_per_isplit = pl.cols_per_isplit;
     a.n_items = (int32_t)pl.n_items;
     a.n_slots = (int32_t)pl.n_slots;
+    a.n_splits = (int32_t)pl.n_splits;
     a.xcd_remap = pl.xcd_remap ? 1 : 0;
 
     int64_t blocks = ceil_div(pl.n_items, kWaves);
