@@ -603,7 +603,7 @@ int make_plan(int ndim, const int64_t* dims, int R, int k, int sbytes, Plan& pl)
     const int64_t steps_in = ceil_div(pl.I_in, 4);
     const int64_t steps_all = pl.o_total * steps_in;
     const int64_t base_items = (int64_t)pl.n_rowblk * pl.n_jchunk * pl.n_batch;
-    const int64_t target = tn.target_items > 0 ? tn.target_items : 8192;
+    const int64_t target = tn.target_items > 0 ? tn.target_items : 12288;   // four per resident wavefront slot at three per SIMD
     const int64_t min_steps = 16;
     int64_t max_steps = tn.max_steps > 0 ? tn.max_steps
                         : (sbytes == 4 ? 1024 : ((int64_t)1 << 40));   // fp32: short accumulation chains
