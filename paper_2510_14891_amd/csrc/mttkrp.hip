@@ -39,9 +39,6 @@ constexpr int kMaxOuter = MTTKRP_MAX_NDIM - 2;
 constexpr int kWaves = 4;           // independent wavefronts per workgroup
 constexpr int kBlockThreads = 64 * kWaves;
 constexpr int kMaxDevices = 16;
-#ifndef MTTKRP_MIN_BLOCKS
-#define MTTKRP_MIN_BLOCKS 2
-#endif
 #ifndef MTTKRP_DEPTH
 #define MTTKRP_DEPTH 4
 #endif
@@ -101,16 +98,34 @@ __device__ __forceinline__ int64_t uni64(int64_t v)
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
+// Register budget of one instantiation (fitted to what the compiler allocates):
+// accumulators take RB*JB*4 values, every step of a batch RB + 2*JB values (X,
+// factor entries, weights), and the rest is about 22 + 20*JB registers in fp64,
+// 26 + 11*JB in fp32.  Aim for four wavefronts per SIMD (128 registers) when four
+// steps per batch still fit, else three (168 registers) with at least two
+// steps, else two (256 registers).
+template <typename T, int RB, int JB> struct Budget {
+    static constexpr int w = (int)sizeof(T) / 4;                 // registers per value
+    static constexpr int acc = RB * JB * 4 * w;
+    static constexpr int fixed = w == 2 ? 22 + 20 * JB : 26 + 11 * JB;
+    static constexpr int per_step = (RB + 2 * JB) * w;
+    static constexpr int fit(int regs) { return (regs - fixed - acc) / per_step; }
+    static constexpr int waves = fit(128 + 8) >= 4 ? 4 : (fit(168 + 8) >= 2 ? 3 : 2);
+    static constexpr int raw = waves == 4 ? fit(128 + 8) : (waves == 3 ? fit(168 + 8) : fit(256));
+    static constexpr int steps = raw > MTTKRP_DEPTH ? MTTKRP_DEPTH : (raw < 2 ? 2 : raw);
+};
+
 // One wavefront = one work item = (row block, column-block chunk, batch value,
 // inner split, outer split).  No LDS, no barriers.
 //
 // Outer column modes: the first one ("mid") is walked by a plain counter; the
 // others ("far") only change when mid wraps, and are then re-derived from the
 // linear outer index by division (rare).
-template <typename T, int RB, int JB, int U>
-__global__ void __launch_bounds__(kBlockThreads, MTTKRP_MIN_BLOCKS)
+template <typename T, int RB, int JB>
+__global__ void __launch_bounds__(kBlockThreads, (Budget<T, RB, JB>::waves))
 mttkrp_stream_kernel(const StreamArgs<T> p)
 {
+    constexpr int U = Budget<T, RB, JB>::steps;   // steps per batch = steps of loads in flight
     typedef Mfma<T> MF;
     typedef typename MF::acc_t acc_t;
 
@@ -441,32 +456,47 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
     }
 }
 
-// M(n, j) = sum over slots of the partial sums, in slot order, in fp64.
+// M(n, j) = sum of the partial sums of all slots, in fp64 and in a fixed order:
+// 16 threads share one output entry, thread q adds slots q, q+16, ... in
+// increasing order, then the 16 subtotals are added in order of q.  A block
+// covers 16 consecutive entries, so each slot is read in contiguous pieces.
 template <typename T>
 __global__ void __launch_bounds__(256)
 mttkrp_combine_kernel(const T* __restrict__ ws, T* __restrict__ M, int64_t n_elems, int R,
                       int n_slots, int64_t stride_row, int64_t stride_slot)
 {
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= n_elems)
-        return;
-    const int64_t n = e / R;
-    const int j = (int)(e - n * R);
-    const T* src = ws + n * stride_row + j;
+    __shared__ double part[16][17];
+    const int el = threadIdx.x & 15;
+    const int sl = threadIdx.x >> 4;
+    const int64_t e = (int64_t)blockIdx.x * 16 + el;
     double s = 0.0;
-    int t = 0;
-    for (; t + 8 <= n_slots; t += 8) {
-        double v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-            v[u] = (double)src[(int64_t)(t + u) * stride_slot];
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-            s += v[u];
+    if (e < n_elems) {
+        const int64_t n = e / R;
+        const int j = (int)(e - n * R);
+        const T* src = ws + n * stride_row + j;
+        int t = sl;
+        for (; t + 48 < n_slots; t += 64) {
+            const double v0 = (double)src[(int64_t)t * stride_slot];
+            const double v1 = (double)src[(int64_t)(t + 16) * stride_slot];
+            const double v2 = (double)src[(int64_t)(t + 32) * stride_slot];
+            const double v3 = (double)src[(int64_t)(t + 48) * stride_slot];
+            s += v0;
+            s += v1;
+            s += v2;
+            s += v3;
+        }
+        for (; t < n_slots; t += 16)
+            s += (double)src[(int64_t)t * stride_slot];
     }
-    for (; t < n_slots; ++t)
-        s += (double)src[(int64_t)t * stride_slot];
-    M[e] = (T)s;
+    part[sl][el] = s;
+    __syncthreads();
+    if (sl == 0 && e < n_elems) {
+        double v = 0.0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+            v += part[q][el];
+        M[e] = (T)v;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -552,7 +582,10 @@ int make_plan(int ndim, const int64_t* dims, int R, int k, int sbytes, Plan& pl)
     {
         int best = 1;
         double best_eff = 0.0;
-        const int rb_max = I0 >= 16 ? (int)(I0 / 16 < 4 ? I0 / 16 : 4) : 1;
+        // fp64 accumulators of more than 12 MFMA tiles do not fit the register file next to the operands
+        const int jb_all = (int)ceil_div(ceil_div(R, 16), ceil_div(ceil_div(R, 16), 4));
+        const int rb_cap = sbytes == 8 && jb_all == 4 ? 3 : 4;
+        const int rb_max = I0 >= 16 ? (int)(I0 / 16 < rb_cap ? I0 / 16 : rb_cap) : 1;
         double eff[5] = {0, 0, 0, 0, 0};
         for (int rb = 1; rb <= rb_max; ++rb) {
             eff[rb] = (double)I0 / (double)(ceil_div(I0, 16 * rb) * 16 * rb);
@@ -680,25 +713,12 @@ int make_plan(int ndim, const int64_t* dims, int R, int k, int sbytes, Plan& pl)
     return MTTKRP_OK;
 }
 
-// Steps per batch (= steps of loads in flight per wavefront): as many as fit
-// next to the accumulators in about 168 registers (three wavefronts per SIMD),
-// between 2 and MTTKRP_DEPTH.
-template <typename T, int RB, int JB> constexpr int batch_steps()
-{
-    constexpr int w = (int)sizeof(T) / 4;                 // registers per value
-    constexpr int acc = RB * JB * 4 * w;
-    constexpr int per_step = (RB + 2 * JB) * w;
-    constexpr int u = (168 - 44 - acc) / per_step;
-    return u < 2 ? 2 : (u > MTTKRP_DEPTH ? MTTKRP_DEPTH : u);
-}
-
 template <typename T, int RB, int JB>
 void launch_stream(const StreamArgs<T>& a, dim3 grid, hipStream_t st)
 {
     // first mode: two wavefront tiles of LDS for the cross-wavefront sum
     const size_t lds = a.first_mode ? (size_t)2 * RB * JB * 4 * 64 * sizeof(T) : 0;
-    hipLaunchKernelGGL((mttkrp_stream_kernel<T, RB, JB, batch_steps<T, RB, JB>()>), grid,
-                       dim3(kBlockThreads), lds, st, a);
+    hipLaunchKernelGGL((mttkrp_stream_kernel<T, RB, JB>), grid, dim3(kBlockThreads), lds, st, a);
 }
 
 template <typename T, int RB>
@@ -863,7 +883,7 @@ int run(int ndim, const int64_t* dims, const T* X, const T* const* factors, int 
         const int64_t stride_slot = k == 0 ? pl.dims[0] * (int64_t)R : R;
         if (timing)
             (void)hipEventRecord(tc->ev[2], st);
-        hipLaunchKernelGGL((mttkrp_combine_kernel<T>), dim3((unsigned)ceil_div(n_elems, 256)),
+        hipLaunchKernelGGL((mttkrp_combine_kernel<T>), dim3((unsigned)ceil_div(n_elems, 16)),
                            dim3(256), 0, st, (const T*)ws, M, n_elems, R, (int)pl.n_slots,
                            stride_row, stride_slot);
         if (timing) {
