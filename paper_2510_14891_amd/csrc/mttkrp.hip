@@ -90,6 +90,13 @@ template <typename T> struct StreamArgs {
 };
 
 
+// Load of a tensor entry.  In fp64 one load instruction covers whole 128-byte
+// lines (16 rows x 8 bytes per column), which are never needed again: a
+// non-temporal load keeps them from displacing the factor rows in L2.  In fp32
+// a line is shared by two load instructions, so it has to stay cacheable.
+__device__ __forceinline__ double stream_load(const double* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ float stream_load(const float* p) { return *p; }
+
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ int64_t uni64(int64_t v)
 {
@@ -286,7 +293,7 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
         const char* be = (const char*)(last ? bbase - b_back : bbase);
 #pragma unroll
         for (int r = 0; r < RB; ++r)
-            xn[r] = __builtin_nontemporal_load(xe + 16 * r);
+            xn[r] = stream_load(xe + 16 * r);
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
             bn[jb] = no_inner ? (T)1 : *(const T*)(be + boff[jb]);
@@ -332,7 +339,7 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
             for (int u = 0; u < U; ++u) {
 #pragma unroll
                 for (int r = 0; r < RB; ++r)
-                    xs[u][r] = __builtin_nontemporal_load(xu + 16 * r);
+                    xs[u][r] = stream_load(xu + 16 * r);
 #pragma unroll
                 for (int jb = 0; jb < JB; ++jb) {
                     bs[u][jb] = *(const T*)(bu + boff[jb]);
