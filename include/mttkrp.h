@@ -112,8 +112,9 @@ void mttkrp_release(void);
 
 /*
  * Measurement hooks (Sec. IV-B reports time per MTTKRP).  While timing is
- * enabled every core / *_ws call records HIP events on its own stream around
- * its streaming kernel and around its combine kernel.  Enabling (re)starts the
+ * enabled every core / *_ws call records three HIP events on its own stream:
+ * before its streaming kernel, between its two kernels and after its combine
+ * kernel (the combine figure therefore includes the gap between the kernels).  Enabling (re)starts the
  * count of timed calls on every device; the most recent 512 timed calls of a
  * device are kept.
  *   mttkrp_timing_count  timed calls on the current device since enabling

@@ -90,12 +90,18 @@ template <typename T> struct StreamArgs {
 };
 
 
-// Load of a tensor entry.  In fp64 one load instruction covers whole 128-byte
-// lines (16 rows x 8 bytes per column), which are never needed again: a
-// non-temporal load keeps them from displacing the factor rows in L2.  In fp32
-// a line is shared by two load instructions, so it has to stay cacheable.
-__device__ __forceinline__ double stream_load(const double* p) { return __builtin_nontemporal_load(p); }
-__device__ __forceinline__ float stream_load(const float* p) { return *p; }
+// Load of a tensor entry.  When every 16-row segment a load instruction reads is
+// a whole, aligned 128-byte line (fp64, I_0 a multiple of 16, aligned X), the line
+// is never needed again and a non-temporal load keeps it from displacing the
+// factor rows in L2.  Otherwise neighbouring load instructions share lines
+// (fp32 segments are half lines, unaligned segments straddle two), and the
+// line has to stay cacheable until its other half has been read.
+template <bool NT, typename T> __device__ __forceinline__ T stream_load(const T* p)
+{
+    if (NT)
+        return __builtin_nontemporal_load(p);
+    return *p;
+}
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ int64_t uni64(int64_t v)
@@ -128,7 +134,7 @@ template <typename T, int RB, int JB> struct Budget {
 // Outer column modes: the first one ("mid") is walked by a plain counter; the
 // others ("far") only change when mid wraps, and are then re-derived from the
 // linear outer index by division (rare).
-template <typename T, int RB, int JB>
+template <typename T, int RB, int JB, bool NT>
 __global__ void __launch_bounds__(kBlockThreads, (Budget<T, RB, JB>::waves))
 mttkrp_stream_kernel(const StreamArgs<T> p)
 {
@@ -293,7 +299,7 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
         const char* be = (const char*)(last ? bbase - b_back : bbase);
 #pragma unroll
         for (int r = 0; r < RB; ++r)
-            xn[r] = stream_load(xe + 16 * r);
+            xn[r] = stream_load<NT>(xe + 16 * r);
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
             bn[jb] = no_inner ? (T)1 : *(const T*)(be + boff[jb]);
@@ -339,7 +345,7 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
             for (int u = 0; u < U; ++u) {
 #pragma unroll
                 for (int r = 0; r < RB; ++r)
-                    xs[u][r] = stream_load(xu + 16 * r);
+                    xs[u][r] = stream_load<NT>(xu + 16 * r);
 #pragma unroll
                 for (int jb = 0; jb < JB; ++jb) {
                     bs[u][jb] = *(const T*)(bu + boff[jb]);
@@ -615,7 +621,7 @@ int make_plan(int ndim, const int64_t* dims, int R, int k, int sbytes, Plan& pl)
     }
 
     // Column modes: all but mode 0 and mode k.  Inner = lowest one with at
-    // least 8 entries, else the largest; the others are outer modes.
+    // least 32 entries (eight steps per sweep), else the largest; the others are outer modes.
     int cols[MTTKRP_MAX_NDIM];
     int n_cols = 0;
     for (int m = 1; m < ndim; ++m)
@@ -623,7 +629,7 @@ int make_plan(int ndim, const int64_t* dims, int R, int k, int sbytes, Plan& pl)
             cols[n_cols++] = m;
     pl.inner = -1;
     for (int c = 0; c < n_cols; ++c)
-        if (dims[cols[c]] >= 8) { pl.inner = cols[c]; break; }
+        if (dims[cols[c]] >= 32) { pl.inner = cols[c]; break; }
     if (pl.inner < 0)
         for (int c = 0; c < n_cols; ++c)
             if (pl.inner < 0 || dims[cols[c]] > dims[pl.inner])
@@ -725,7 +731,12 @@ void launch_stream(const StreamArgs<T>& a, dim3 grid, hipStream_t st)
 {
     // first mode: two wavefront tiles of LDS for the cross-wavefront sum
     const size_t lds = a.first_mode ? (size_t)2 * RB * JB * 4 * 64 * sizeof(T) : 0;
-    hipLaunchKernelGGL((mttkrp_stream_kernel<T, RB, JB>), grid, dim3(kBlockThreads), lds, st, a);
+    // non-temporal tensor loads only when each load instruction reads whole aligned lines
+    const bool nt = sizeof(T) == 8 && a.I0 % 16 == 0 && ((uintptr_t)a.X & 127u) == 0;
+    if (nt)
+        hipLaunchKernelGGL((mttkrp_stream_kernel<T, RB, JB, true>), grid, dim3(kBlockThreads), lds, st, a);
+    else
+        hipLaunchKernelGGL((mttkrp_stream_kernel<T, RB, JB, false>), grid, dim3(kBlockThreads), lds, st, a);
 }
 
 template <typename T, int RB>
@@ -753,7 +764,8 @@ void launch_stream_rb(int RB, int JB, const StreamArgs<T>& a, dim3 grid, hipStre
 constexpr int kTimingSlots = 512;   // ring of timed calls kept per device
 
 struct TimedCall {
-    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};   // stream begin/end, combine begin/end
+    // before the streaming kernel, between the two kernels, after the combine kernel
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     bool combine = false;
 };
 
@@ -822,7 +834,7 @@ int run(int ndim, const int64_t* dims, const T* X, const T* const* factors, int 
             if (!calls)
                 return MTTKRP_ERR_DEVICE;
             for (int c = 0; c < kTimingSlots; ++c)
-                for (int e = 0; e < 4; ++e)
+                for (int e = 0; e < 3; ++e)
                     if (hipEventCreate(&calls[c].ev[e]) != hipSuccess) {
                         delete[] calls;   // events created so far are leaked; creation does not fail in practice
                         return MTTKRP_ERR_DEVICE;
@@ -888,13 +900,11 @@ int run(int ndim, const int64_t* dims, const T* X, const T* const* factors, int 
         const int64_t n_elems = pl.dims[k] * (int64_t)R;
         const int64_t stride_row = k == 0 ? R : pl.n_slots * (int64_t)R;
         const int64_t stride_slot = k == 0 ? pl.dims[0] * (int64_t)R : R;
-        if (timing)
-            (void)hipEventRecord(tc->ev[2], st);
         hipLaunchKernelGGL((mttkrp_combine_kernel<T>), dim3((unsigned)ceil_div(n_elems, 16)),
                            dim3(256), 0, st, (const T*)ws, M, n_elems, R, (int)pl.n_slots,
                            stride_row, stride_slot);
         if (timing) {
-            (void)hipEventRecord(tc->ev[3], st);
+            (void)hipEventRecord(tc->ev[2], st);
             tc->combine = true;
         }
         if (hipGetLastError() != hipSuccess)
@@ -976,7 +986,7 @@ void mttkrp_release(void)
         ds.ws_bytes = 0;
         if (ds.calls) {
             for (int c = 0; c < kTimingSlots; ++c)
-                for (int e = 0; e < 4; ++e)
+                for (int e = 0; e < 3; ++e)
                     (void)hipEventDestroy(ds.calls[c].ev[e]);
             delete[] ds.calls;
         }
@@ -1020,11 +1030,11 @@ int mttkrp_timing_get(int64_t index, float* stream_ms, float* combine_ms)
         return MTTKRP_ERR_INVALID_ARG;
     TimedCall& tc = ds.calls[index % kTimingSlots];
     *combine_ms = 0.0f;
-    if (hipEventSynchronize(tc.combine ? tc.ev[3] : tc.ev[1]) != hipSuccess)
+    if (hipEventSynchronize(tc.combine ? tc.ev[2] : tc.ev[1]) != hipSuccess)
         return MTTKRP_ERR_DEVICE;
     if (hipEventElapsedTime(stream_ms, tc.ev[0], tc.ev[1]) != hipSuccess)
         return MTTKRP_ERR_DEVICE;
-    if (tc.combine && hipEventElapsedTime(combine_ms, tc.ev[2], tc.ev[3]) != hipSuccess)
+    if (tc.combine && hipEventElapsedTime(combine_ms, tc.ev[1], tc.ev[2]) != hipSuccess)
         return MTTKRP_ERR_DEVICE;
     return MTTKRP_OK;
 }
