@@ -25,7 +25,8 @@
  * the caller.  dims and the factors pointer array are HOST arrays, read before
  * the call returns.  The library keeps no reference to any argument after the
  * call returns (the enqueued kernels do, until the stream has drained).
- * stream is a hipStream_t passed as void* (NULL = the default stream).
+ * stream is a hipStream_t passed as void* (NULL = the default stream).  The
+ * device that holds the pointers and the stream must be the current device.
  *
  * Semantics: M is overwritten (never accumulated into).  factors[k] is never
  * read and may be NULL (Eq. (elem) excludes m = k).  M must not alias an
@@ -99,6 +100,32 @@ int mttkrp_dense_f64_ws(int ndim, const int64_t* dims, const double* X,
                         void* workspace, size_t workspace_bytes, void* stream);
 int mttkrp_dense_f32_ws(int ndim, const int64_t* dims, const float* X,
                         const float* const* factors, int R, int k, float* M,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Extended calls: the MTTKRP exactly as the paper states it, Eq. (krp) / Eq.
+ * (elem) with the weight vector, plus optional accumulation:
+ *
+ *     M = beta * M + X_(k) (Khatri-Rao of all A_m, m != k) diag(lambda)
+ *
+ *   lambda   device, R values, or NULL for lambda = 1
+ *   beta     host scalar; with beta = 0 the old contents of M are never read
+ *   workspace, workspace_bytes   caller-owned workspace as in the *_ws calls
+ *            (size from mttkrp_dense_ex_workspace_bytes, never 0), or
+ *            NULL / 0 to use the library-owned one
+ * With lambda = NULL and beta = 0 the result equals that of the core calls bit
+ * for bit.  Everything else (layouts, ownership, errors, asynchrony) is as for
+ * the core calls.
+ */
+size_t mttkrp_dense_ex_workspace_bytes(int ndim, const int64_t* dims, int R, int k,
+                                       int dtype_bytes);
+int mttkrp_dense_f64_ex(int ndim, const int64_t* dims, const double* X,
+                        const double* const* factors, int R, int k,
+                        const double* lambda, double beta, double* M,
+                        void* workspace, size_t workspace_bytes, void* stream);
+int mttkrp_dense_f32_ex(int ndim, const int64_t* dims, const float* X,
+                        const float* const* factors, int R, int k,
+                        const float* lambda, float beta, float* M,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /* Static, human-readable text for a status code. */

@@ -6,11 +6,13 @@
  * code, header, table or helper with the HIP library and must stay that way.
  *
  * What it computes is the element-wise definition of the MTTKRP (paper
- * Sec. II-B, Eq. (elem)) with the weight vector lambda fixed to one:
+ * Sec. II-B, Eq. (elem)):
  *
- *     M(n, j) = sum over all multi-indices i with i_k = n of
+ *     M(n, j) = lambda_j * sum over all multi-indices i with i_k = n of
  *               X(i) * prod_{m != k} A_m(i_m, j)
  *
+ * with the weight vector lambda optional (NULL means lambda = 1, which is the
+ * hot path of the library under test),
  * written out as a plain loop over every tensor entry.  No blocking, no
  * factoring of the product, no re-association beyond "one running sum per
  * output entry, in storage order of X".
@@ -109,7 +111,7 @@ static int check_args(int ndim, const int64_t *dims, const void *X,
 #define DEFINE_ORACLE(NAME, T, ACC)                                            \
 int NAME(int ndim, const int64_t *dims, const T *X,                            \
          const T *const *factors, int R, int k,                                \
-         const int64_t *rows, int64_t nrows, T *M)                             \
+         const int64_t *rows, int64_t nrows, const T *lambda, T *M)            \
 {                                                                              \
     int rc = check_args(ndim, dims, X, (const void *const *)factors, R, k,     \
                         rows, nrows, M);                                       \
@@ -180,8 +182,12 @@ int NAME(int ndim, const int64_t *dims, const T *X,                            \
                 idx[m] = 0;                                                    \
             }                                                                  \
         }                                                                      \
-        for (int64_t j = j0; j < j1; ++j)                                      \
-            M[t * (int64_t)R + j] = (T)acc[j - j0];                            \
+        for (int64_t j = j0; j < j1; ++j) {                                    \
+            ACC v = acc[j - j0];                                               \
+            if (lambda)                                                        \
+                v = (ACC)lambda[j] * v;                                        \
+            M[t * (int64_t)R + j] = (T)v;                                      \
+        }                                                                      \
         free(acc);                                                             \
     }                                                                          \
     return failed ? ORACLE_NO_MEM : ORACLE_OK;                                 \

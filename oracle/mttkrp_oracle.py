@@ -45,7 +45,8 @@ def _load():
             fn.restype = ctypes.c_int
             fn.argtypes = [ctypes.c_int, i64p, ctypes.c_void_p,
                            ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
-                           ctypes.c_int, i64p, ctypes.c_int64, ctypes.c_void_p]
+                           ctypes.c_int, i64p, ctypes.c_int64, ctypes.c_void_p,
+                           ctypes.c_void_p]
         lib.oracle_max_threads.restype = ctypes.c_int
         lib.oracle_long_double_mant_bits.restype = ctypes.c_int
         _lib = lib
@@ -62,9 +63,10 @@ def long_double_mant_bits() -> int:
 
 
 def mttkrp(X: np.ndarray, factors: Sequence[Optional[np.ndarray]], k: int,
-           rows: Optional[Sequence[int]] = None, native_acc: bool = False
-           ) -> np.ndarray:
-    """Mode-``k`` (0-based) MTTKRP of a dense tensor, Eq. (elem) with lambda=1.
+           rows: Optional[Sequence[int]] = None, native_acc: bool = False,
+           lam: Optional[np.ndarray] = None) -> np.ndarray:
+    """Mode-``k`` (0-based) MTTKRP of a dense tensor, Eq. (elem); lambda = 1
+    unless ``lam`` (R weights) is given.
 
     X        numpy array of shape (I_0, ..., I_{d-1}); its logical entry
              X[i_0, ..., i_{d-1}] is what the definition sums.  It is laid out
@@ -119,8 +121,14 @@ def mttkrp(X: np.ndarray, factors: Sequence[Optional[np.ndarray]], k: int,
         nrows = rows_arr.size
         rows_p = rows_arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
     M = np.zeros((nrows, R), dtype=ct)
+    lam_p = None
+    if lam is not None:
+        lam_arr = np.ascontiguousarray(lam, dtype=ct)
+        if lam_arr.shape != (R,):
+            raise ValueError("lam must hold R weights")
+        lam_p = lam_arr.ctypes.data
     fn = getattr(lib, "oracle_mttkrp_" + suffix + ("_native" if native_acc else ""))
-    rc = fn(d, dims, Xf.ctypes.data, ptrs, R, k, rows_p, nrows, M.ctypes.data)
+    rc = fn(d, dims, Xf.ctypes.data, ptrs, R, k, rows_p, nrows, lam_p, M.ctypes.data)
     if rc != 0:
         raise RuntimeError("oracle returned %d" % rc)
     return M

@@ -26,7 +26,8 @@ MTTKRP_MAX_NDIM = 8
 # every symbol include/mttkrp.h declares
 EXPORTED = (
     "mttkrp_dense_f64", "mttkrp_dense_f32", "mttkrp_dense_workspace_bytes",
-    "mttkrp_dense_f64_ws", "mttkrp_dense_f32_ws", "mttkrp_status_string",
+    "mttkrp_dense_f64_ws", "mttkrp_dense_f32_ws", "mttkrp_dense_ex_workspace_bytes",
+    "mttkrp_dense_f64_ex", "mttkrp_dense_f32_ex", "mttkrp_status_string",
     "mttkrp_version", "mttkrp_release", "mttkrp_timing_enable",
     "mttkrp_timing_count", "mttkrp_timing_get", "mttkrp_timing_last",
     "mttkrp_tune_set", "mttkrp_plan_describe",
@@ -65,6 +66,15 @@ def lib() -> ctypes.CDLL:
     L.mttkrp_dense_workspace_bytes.restype = ctypes.c_size_t
     L.mttkrp_dense_workspace_bytes.argtypes = [ctypes.c_int, i64p, ctypes.c_int,
                                                ctypes.c_int, ctypes.c_int]
+    L.mttkrp_dense_ex_workspace_bytes.restype = ctypes.c_size_t
+    L.mttkrp_dense_ex_workspace_bytes.argtypes = L.mttkrp_dense_workspace_bytes.argtypes
+    ex = [ctypes.c_int, i64p, ctypes.c_void_p, vpp, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    L.mttkrp_dense_f64_ex.restype = ctypes.c_int
+    L.mttkrp_dense_f64_ex.argtypes = ex + [ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_size_t, ctypes.c_void_p]
+    L.mttkrp_dense_f32_ex.restype = ctypes.c_int
+    L.mttkrp_dense_f32_ex.argtypes = ex + [ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_size_t, ctypes.c_void_p]
     L.mttkrp_status_string.restype = ctypes.c_char_p
     L.mttkrp_status_string.argtypes = [ctypes.c_int]
     L.mttkrp_version.restype = ctypes.c_int
@@ -149,8 +159,16 @@ def mttkrp_dense_workspace_bytes(dims: Sequence[int], R: int, k: int, dtype_byte
     return int(n)
 
 
+def mttkrp_dense_ex_workspace_bytes(dims: Sequence[int], R: int, k: int, dtype_bytes: int) -> int:
+    n = lib().mttkrp_dense_ex_workspace_bytes(len(dims), _dims_array(dims), int(R), int(k),
+                                              int(dtype_bytes))
+    if n == ctypes.c_size_t(-1).value:
+        raise MttkrpError(MTTKRP_ERR_INVALID_ARG, "invalid argument")
+    return int(n)
+
+
 def mttkrp_dense(X, dims: Sequence[int], factors: Sequence, k: int, M=None,
-                 workspace=None, stream: Optional[int] = None):
+                 workspace=None, stream: Optional[int] = None, lam=None, beta=None):
     """M = X_(k) (Khatri-Rao of all factors but the k-th), on the GPU.
 
     X        flat torch tensor on a HIP device, prod(dims) values, first index
@@ -162,6 +180,9 @@ def mttkrp_dense(X, dims: Sequence[int], factors: Sequence, k: int, M=None,
     M        optional output tensor (I_k, R); allocated when None
     workspace  optional torch tensor to use as caller-owned workspace (selects
              the *_ws entry point)
+    lam, beta  optional weight vector (torch tensor of R values on the device)
+             and accumulation factor; either selects the *_ex entry point:
+             M = beta * M + result * diag(lam)
     stream   raw hipStream_t value; default: torch's current stream
     Returns M.  The call is asynchronous on the stream.
     """
@@ -211,8 +232,19 @@ def mttkrp_dense(X, dims: Sequence[int], factors: Sequence, k: int, M=None,
             raise ValueError("M must be a contiguous (I_k, R) tensor like X")
     if stream is None:
         stream = torch.cuda.current_stream(X.device).cuda_stream
+    if lam is not None and (lam.dtype != X.dtype or lam.device != X.device
+                            or not lam.is_contiguous() or lam.numel() != R):
+        raise ValueError("lam must be a contiguous device vector of R values like X")
     with torch.cuda.device(X.device):
-        if workspace is None:
+        if lam is not None or beta is not None:
+            rc = getattr(L, "mttkrp_dense_" + suffix + "_ex")(
+                d, _dims_array(dims), X.data_ptr(), ptrs, R, int(k),
+                lam.data_ptr() if lam is not None else None,
+                float(beta) if beta is not None else 0.0, M.data_ptr(),
+                workspace.data_ptr() if workspace is not None else None,
+                workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                ctypes.c_void_p(stream))
+        elif workspace is None:
             rc = getattr(L, "mttkrp_dense_" + suffix)(
                 d, _dims_array(dims), X.data_ptr(), ptrs, R, int(k), M.data_ptr(),
                 ctypes.c_void_p(stream))

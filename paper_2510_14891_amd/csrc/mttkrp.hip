@@ -476,7 +476,8 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
 template <typename T>
 __global__ void __launch_bounds__(256)
 mttkrp_combine_kernel(const T* __restrict__ ws, T* __restrict__ M, int64_t n_elems, int R,
-                      int n_slots, int64_t stride_row, int64_t stride_slot)
+                      int n_slots, int64_t stride_row, int64_t stride_slot,
+                      const T* __restrict__ lambda, double beta)
 {
     __shared__ double part[16][17];
     const int el = threadIdx.x & 15;
@@ -508,6 +509,10 @@ mttkrp_combine_kernel(const T* __restrict__ ws, T* __restrict__ M, int64_t n_ele
 #pragma unroll
         for (int q = 0; q < 16; ++q)
             v += part[q][el];
+        if (lambda)                      // Eq. (krp): ... diag(lambda)
+            v *= (double)lambda[e % R];
+        if (beta != 0.0)                 // M is read only when it is accumulated into
+            v += beta * (double)M[e];
         M[e] = (T)v;
     }
 }
@@ -780,7 +785,8 @@ bool g_timing = false;
 
 template <typename T>
 int run(int ndim, const int64_t* dims, const T* X, const T* const* factors, int R, int k, T* M,
-        void* workspace, size_t workspace_bytes, bool own_ws, void* stream)
+        void* workspace, size_t workspace_bytes, bool own_ws, void* stream,
+        const T* lambda = nullptr, double beta = 0.0)
 {
     if (!X || !M || !factors)
         return MTTKRP_ERR_INVALID_ARG;
@@ -788,6 +794,10 @@ int run(int ndim, const int64_t* dims, const T* X, const T* const* factors, int 
     int rc = make_plan(ndim, dims, R, k, (int)sizeof(T), pl);
     if (rc != MTTKRP_OK)
         return rc;
+    // Weights and accumulation are applied by the combine kernel, which then always runs.
+    const bool scaled = lambda != nullptr || beta != 0.0;
+    if (scaled && pl.ws_bytes == 0)
+        pl.ws_bytes = (size_t)pl.dims[k] * (size_t)R * sizeof(T);
     for (int m = 0; m < ndim; ++m)
         if (m != k && !factors[m])
             return MTTKRP_ERR_INVALID_ARG;
@@ -862,7 +872,7 @@ int run(int ndim, const int64_t* dims, const T* X, const T* const* factors, int 
         a.sx_out[m] = pl.strides[pl.out_modes[m]];
         a.dim_out[m] = (int32_t)pl.dims[pl.out_modes[m]];
     }
-    a.out = pl.n_slots > 1 ? ws : M;
+    a.out = pl.ws_bytes > 0 ? ws : M;
     a.o_total = pl.o_total;
     a.o_per_item = pl.o_per_item;
     a.n_out = pl.n_out;
@@ -896,13 +906,13 @@ int run(int ndim, const int64_t* dims, const T* X, const T* const* factors, int 
     }
     if (hipGetLastError() != hipSuccess)
         return MTTKRP_ERR_DEVICE;
-    if (pl.n_slots > 1) {
+    if (pl.ws_bytes > 0) {
         const int64_t n_elems = pl.dims[k] * (int64_t)R;
         const int64_t stride_row = k == 0 ? R : pl.n_slots * (int64_t)R;
         const int64_t stride_slot = k == 0 ? pl.dims[0] * (int64_t)R : R;
         hipLaunchKernelGGL((mttkrp_combine_kernel<T>), dim3((unsigned)ceil_div(n_elems, 16)),
                            dim3(256), 0, st, (const T*)ws, M, n_elems, R, (int)pl.n_slots,
-                           stride_row, stride_slot);
+                           stride_row, stride_slot, lambda, beta);
         if (timing) {
             (void)hipEventRecord(tc->ev[2], st);
             tc->combine = true;
@@ -951,6 +961,31 @@ int mttkrp_dense_f32_ws(int ndim, const int64_t* dims, const float* X, const flo
                         void* stream)
 {
     return run<float>(ndim, dims, X, factors, R, k, M, workspace, workspace_bytes, false, stream);
+}
+
+size_t mttkrp_dense_ex_workspace_bytes(int ndim, const int64_t* dims, int R, int k, int dtype_bytes)
+{
+    Plan pl;
+    if (make_plan(ndim, dims, R, k, dtype_bytes, pl) != MTTKRP_OK)
+        return (size_t)-1;
+    return pl.ws_bytes > 0 ? pl.ws_bytes : (size_t)pl.dims[k] * (size_t)R * (size_t)dtype_bytes;
+}
+
+int mttkrp_dense_f64_ex(int ndim, const int64_t* dims, const double* X,
+                        const double* const* factors, int R, int k, const double* lambda,
+                        double beta, double* M, void* workspace, size_t workspace_bytes,
+                        void* stream)
+{
+    return run<double>(ndim, dims, X, factors, R, k, M, workspace, workspace_bytes,
+                       workspace == nullptr, stream, lambda, beta);
+}
+
+int mttkrp_dense_f32_ex(int ndim, const int64_t* dims, const float* X, const float* const* factors,
+                        int R, int k, const float* lambda, float beta, float* M, void* workspace,
+                        size_t workspace_bytes, void* stream)
+{
+    return run<float>(ndim, dims, X, factors, R, k, M, workspace, workspace_bytes,
+                      workspace == nullptr, stream, lambda, (double)beta);
 }
 
 const char* mttkrp_status_string(int status)

@@ -364,3 +364,34 @@ def test_cp_noise_recipe_small():
     rms = np.sqrt(np.mean(Xcp ** 2))
     ratio = np.sqrt(np.mean((X - Xcp) ** 2)) / rms
     assert 0.005 < ratio < 0.02
+
+
+# ---------------------------------------------------------------- weight vector lambda
+def test_lambda_is_a_column_scaling(oracle):
+    """Eq. (krp): G = Y_(k) Z diag(lambda); Eq. (elem): the factor lambda_j."""
+    dims, R, S = (6, 5, 4), 4, 3
+    X, A = rand_problem(dims, R, seed=97)
+    lam = np.array([0.5, -2.0, 3.0, 1.25])
+    for k in range(3):
+        base = oracle.mttkrp(X, A, k)
+        assert np.array_equal(oracle.mttkrp(X, A, k, lam=np.ones(R)), base)
+        assert oracle.normwise_rel_err(oracle.mttkrp(X, A, k, lam=lam), base * lam) <= 1e-15
+        # against the matrix-based definition with the explicit diag(lambda)
+        ref = mttkrp_matrix_based(X, A, k) @ np.diag(lam)
+        assert oracle.normwise_rel_err(oracle.mttkrp(X, A, k, lam=lam), ref) <= 1e-14
+    # closed form: X = [[mu; U_0, U_1, U_2]]  =>  M = U_k diag(mu) (hadamard U_m^T A_m) diag(lambda)
+    U = [inputs.normal(700 + m, (I, S)).numpy() for m, I in enumerate(dims)]
+    mu = np.array([2.0, 0.5, -1.0])
+    Xk = np.zeros(dims)
+    for s in range(S):
+        t = mu[s] * U[0][:, s]
+        for m in range(1, 3):
+            t = np.multiply.outer(t, U[m][:, s])
+        Xk += t
+    for k in range(3):
+        H = np.ones((S, R))
+        for m in range(3):
+            if m != k:
+                H = H * (U[m].T @ A[m])
+        ref = (U[k] * mu) @ H * lam
+        assert oracle.normwise_rel_err(oracle.mttkrp(Xk, A, k, lam=lam), ref) <= 1e-13

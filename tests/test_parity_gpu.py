@@ -258,3 +258,54 @@ def test_non_default_stream(mt, oracle):
         M = mt.mttkrp_dense(Xd, dims, Ad, 1)
     st.synchronize()
     assert oracle.normwise_rel_err(M.cpu().numpy(), ref) <= 1e-12
+
+
+# ---------------------------------------------------------------- extended calls and high rank
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+def test_ex_lambda_and_beta(mt, oracle, dtype):
+    """M = beta * M + X_(k) Z diag(lambda) (Eq. (krp) with its weight vector)."""
+    dims, R = (130, 21, 10, 6), 20
+    X, A = make_problem(dims, R, dtype, seed=51)
+    lam = inputs.uniform(52, R, 0.5, 2.0, dtype=dtype)
+    Xd, Ad, lamd = X.cuda(), [a.cuda() for a in A], lam.cuda()
+    for k in range(4):
+        M0 = inputs.uniform(60 + k, (dims[k], R), -1.0, 1.0, dtype=dtype)
+        ref_lam = oracle_mttkrp(oracle, X, dims, A, k)   # lambda = 1
+        ref = oracle.mttkrp(inputs.as_ndarray_view(X, dims), [a.numpy() for a in A], k,
+                            lam=lam.numpy())
+        # lambda only
+        got = mt.mttkrp_dense(Xd, dims, Ad, k, lam=lamd).cpu().numpy()
+        assert oracle.normwise_rel_err(got, ref) <= TOL[dtype]
+        # lambda = 1, beta = 0 through the extended call: bit-identical to the core call
+        plain = mt.mttkrp_dense(Xd, dims, Ad, k).cpu().numpy()
+        via_ex = mt.mttkrp_dense(Xd, dims, Ad, k, beta=0.0).cpu().numpy()
+        assert np.array_equal(plain, via_ex)
+        assert oracle.normwise_rel_err(plain, ref_lam) <= TOL[dtype]
+        # accumulation, with a caller-owned workspace
+        beta = -0.75
+        Md = M0.cuda()
+        ws = torch.empty(mt.mttkrp_dense_ex_workspace_bytes(dims, R, k, X.element_size()),
+                         dtype=torch.uint8, device="cuda")
+        mt.mttkrp_dense(Xd, dims, Ad, k, M=Md, lam=lamd, beta=beta, workspace=ws)
+        want = beta * M0.numpy().astype(np.float64) + ref.astype(np.float64)
+        assert oracle.normwise_rel_err(Md.cpu().numpy(), want) <= TOL[dtype]
+        # beta = 0 never reads M: NaNs in M do not leak
+        Mn = torch.full((dims[k], R), float("nan"), dtype=dtype, device="cuda")
+        mt.mttkrp_dense(Xd, dims, Ad, k, M=Mn, lam=lamd, beta=0.0)
+        assert oracle.normwise_rel_err(Mn.cpu().numpy(), ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("R", [500, 1000])
+def test_high_rank(mt, oracle, R):
+    """The paper's flagship regime (Sec. IV: R = 500 ... 2000): many 64-column chunks."""
+    dims = (70, 20, 12, 9)
+    X, A = make_problem(dims, R, torch.float64, seed=71)
+    for k in range(4):
+        got = gpu_mttkrp(mt, X, dims, A, k)
+        ref = oracle_mttkrp(oracle, X, dims, A, k)
+        assert oracle.normwise_rel_err(got, ref) <= 1e-12
+    # the extra memory stays in the O(R sum I_n) class, far below the Khatri-Rao matrix
+    for k in range(4):
+        ws = mt.mttkrp_dense_workspace_bytes((401, 201, 12, 501), 2000, k, 8)
+        krp = (401 * 201 * 12 * 501 // (401, 201, 12, 501)[k]) * 2000 * 8
+        assert ws <= 128 << 20 and ws < krp / 100
