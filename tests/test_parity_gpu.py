@@ -26,8 +26,12 @@ def mt():
     from paper_2510_14891_amd import binding
     binding.lib()   # raises if the HIP library was not built: no silent fallback
     yield binding
-    for key in ("row_blocks", "target_items", "max_steps", "xcd_remap", "ws_percent"):
+    for key in TUNE_KEYS:
         binding.mttkrp_tune_set(key, 0)
+
+
+TUNE_KEYS = ("row_blocks", "target_items", "max_steps", "xcd_remap", "ws_percent",
+             "max_col_blocks", "first_group")
 
 
 def make_problem(dims, R, dtype, seed, dist=("uniform", -1.0, 1.0)):
@@ -228,7 +232,9 @@ def test_result_does_not_depend_on_the_decomposition(mt, oracle, dtype):
     settings = [
         {"row_blocks": 1}, {"row_blocks": 2}, {"row_blocks": 3}, {"row_blocks": 4},
         {"target_items": 1}, {"target_items": 64}, {"target_items": 100000},
-        {"max_steps": 8}, {"xcd_remap": 2}, {"ws_percent": 100, "target_items": 50000},
+        {"max_steps": 8}, {"xcd_remap": 1}, {"ws_percent": 100, "target_items": 50000},
+        {"max_col_blocks": 1}, {"first_group": 1}, {"first_group": 4},
+        {"first_group": 1, "ws_percent": 100, "target_items": 50000},
     ]
     try:
         for st in settings:
@@ -242,7 +248,7 @@ def test_result_does_not_depend_on_the_decomposition(mt, oracle, dtype):
             for key in st:
                 mt.mttkrp_tune_set(key, 0)
     finally:
-        for key in ("row_blocks", "target_items", "max_steps", "xcd_remap", "ws_percent"):
+        for key in TUNE_KEYS:
             mt.mttkrp_tune_set(key, 0)
 
 
