@@ -171,6 +171,9 @@ int mttkrp_timing_last(float* stream_ms, float* combine_ms);
  *   "first_group"   first mode only: 4 = the four wavefronts of a workgroup sum
  *                   their tiles in LDS and write one partial tile, 1 = every
  *                   wavefront writes its own partial tile, 0 = chosen per shape
+ *   "waves_per_simd"  cap on resident wavefronts per SIMD (2..7; enforced by
+ *                   reserving LDS), 0 = whatever the registers allow
+ *   "nt_loads"      1 = never use non-temporal tensor loads, 0 = chosen by alignment
  * Returns MTTKRP_ERR_INVALID_ARG for an unknown key or a value out of range.
  */
 int mttkrp_tune_set(const char* key, int64_t value);

@@ -21,8 +21,12 @@ HIPCC_FLAGS = [
 def build(force: bool = True, verbose: bool = False) -> str:
     """Compile csrc/mttkrp.hip into libmttkrp_hip.so next to this file."""
     if (not force and os.path.exists(LIB)
-            and os.path.getmtime(LIB) >= max(os.path.getmtime(SRC), os.path.getmtime(HEADER))):
+            and os.path.getmtime(LIB) >= max(os.path.getmtime(SRC), os.path.getmtime(HEADER),
+                                             os.path.getmtime(os.path.join(HERE, "csrc", "gen_pipe.py")))):
         return LIB
+    # regenerate the inline-assembly include (deterministic; the result is committed too)
+    subprocess.run([sys.executable, os.path.join(HERE, "csrc", "gen_pipe.py")], check=True,
+                   stdout=subprocess.DEVNULL)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB, SRC]
     if verbose:

@@ -75,343 +75,25 @@ template <> struct Mfma<float> {
 // outstanding loads conservatively around control flow, which keeps a wavefront
 // from overlapping its own loads with its own MFMAs; this hand-scheduled loop
 // keeps three steps of loads in flight while the MFMAs of a fourth run.  It
-// covers n = 3 + 4 * n_loop consecutive unmasked steps of one sweep: X pointer
+// covers n = 3 + 4 * n_loop + rem consecutive unmasked steps of one sweep: X pointer
 // and factor offsets advance by constant strides, one weight Q per column block.
 // Temporaries live in fixed registers (declared as clobbers); the loads of step
 // t go to operand set t mod 4; every wait names how many later loads may still
 // be outstanding (memory operations return in issue order).
-// generated by a script (ring of 4 operand sets in v[116:167], 3 steps in flight)
-#define MTTKRP_PIPE_D42_ASM_NT \
-    "s_nop 4\n" \
-    "global_load_dwordx2 v[116:117], %[xq], off nt\n" \
-    "global_load_dwordx2 v[118:119], %[xq], off offset:128 nt\n" \
-    "global_load_dwordx2 v[120:121], %[xq], off offset:256 nt\n" \
-    "global_load_dwordx2 v[122:123], %[xq], off offset:384 nt\n" \
-    "global_load_dwordx2 v[124:125], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[126:127], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "global_load_dwordx2 v[128:129], %[xq], off nt\n" \
-    "global_load_dwordx2 v[130:131], %[xq], off offset:128 nt\n" \
-    "global_load_dwordx2 v[132:133], %[xq], off offset:256 nt\n" \
-    "global_load_dwordx2 v[134:135], %[xq], off offset:384 nt\n" \
-    "global_load_dwordx2 v[136:137], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[138:139], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "global_load_dwordx2 v[140:141], %[xq], off nt\n" \
-    "global_load_dwordx2 v[142:143], %[xq], off offset:128 nt\n" \
-    "global_load_dwordx2 v[144:145], %[xq], off offset:256 nt\n" \
-    "global_load_dwordx2 v[146:147], %[xq], off offset:384 nt\n" \
-    "global_load_dwordx2 v[148:149], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[150:151], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "s_cmp_eq_u32 %[n], 0\n" \
-    "s_cbranch_scc1 2f\n" \
-    "1:\n" \
-    "global_load_dwordx2 v[152:153], %[xq], off nt\n" \
-    "global_load_dwordx2 v[154:155], %[xq], off offset:128 nt\n" \
-    "global_load_dwordx2 v[156:157], %[xq], off offset:256 nt\n" \
-    "global_load_dwordx2 v[158:159], %[xq], off offset:384 nt\n" \
-    "global_load_dwordx2 v[160:161], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[162:163], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "s_waitcnt vmcnt(18)\n" \
-    "v_mul_f64 v[164:165], v[124:125], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[126:127], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[116:117], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[116:117], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[118:119], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[118:119], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[120:121], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[120:121], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[122:123], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[122:123], v[166:167], %[a31]\n" \
-    "global_load_dwordx2 v[116:117], %[xq], off nt\n" \
-    "global_load_dwordx2 v[118:119], %[xq], off offset:128 nt\n" \
-    "global_load_dwordx2 v[120:121], %[xq], off offset:256 nt\n" \
-    "global_load_dwordx2 v[122:123], %[xq], off offset:384 nt\n" \
-    "global_load_dwordx2 v[124:125], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[126:127], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "s_waitcnt vmcnt(18)\n" \
-    "v_mul_f64 v[164:165], v[136:137], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[138:139], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[128:129], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[128:129], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[130:131], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[130:131], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[132:133], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[132:133], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[134:135], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[134:135], v[166:167], %[a31]\n" \
-    "global_load_dwordx2 v[128:129], %[xq], off nt\n" \
-    "global_load_dwordx2 v[130:131], %[xq], off offset:128 nt\n" \
-    "global_load_dwordx2 v[132:133], %[xq], off offset:256 nt\n" \
-    "global_load_dwordx2 v[134:135], %[xq], off offset:384 nt\n" \
-    "global_load_dwordx2 v[136:137], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[138:139], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "s_waitcnt vmcnt(18)\n" \
-    "v_mul_f64 v[164:165], v[148:149], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[150:151], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[140:141], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[140:141], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[142:143], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[142:143], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[144:145], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[144:145], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[146:147], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[146:147], v[166:167], %[a31]\n" \
-    "global_load_dwordx2 v[140:141], %[xq], off nt\n" \
-    "global_load_dwordx2 v[142:143], %[xq], off offset:128 nt\n" \
-    "global_load_dwordx2 v[144:145], %[xq], off offset:256 nt\n" \
-    "global_load_dwordx2 v[146:147], %[xq], off offset:384 nt\n" \
-    "global_load_dwordx2 v[148:149], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[150:151], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "s_waitcnt vmcnt(18)\n" \
-    "v_mul_f64 v[164:165], v[160:161], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[162:163], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[152:153], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[152:153], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[154:155], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[154:155], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[156:157], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[156:157], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[158:159], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[158:159], v[166:167], %[a31]\n" \
-    "s_sub_u32 %[n], %[n], 1\n" \
-    "s_cmp_lg_u32 %[n], 0\n" \
-    "s_cbranch_scc1 1b\n" \
-    "2:\n" \
-    "s_waitcnt vmcnt(12)\n" \
-    "v_mul_f64 v[164:165], v[124:125], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[126:127], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[116:117], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[116:117], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[118:119], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[118:119], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[120:121], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[120:121], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[122:123], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[122:123], v[166:167], %[a31]\n" \
-    "s_waitcnt vmcnt(6)\n" \
-    "v_mul_f64 v[164:165], v[136:137], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[138:139], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[128:129], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[128:129], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[130:131], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[130:131], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[132:133], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[132:133], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[134:135], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[134:135], v[166:167], %[a31]\n" \
-    "s_waitcnt vmcnt(0)\n" \
-    "v_mul_f64 v[164:165], v[148:149], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[150:151], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[140:141], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[140:141], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[142:143], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[142:143], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[144:145], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[144:145], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[146:147], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[146:147], v[166:167], %[a31]\n" \
-    "s_nop 7\n" \
-    "s_nop 7\n" \
-    "s_nop 7\n"
-#define MTTKRP_PIPE_D42_ASM \
-    "s_nop 4\n" \
-    "global_load_dwordx2 v[116:117], %[xq], off\n" \
-    "global_load_dwordx2 v[118:119], %[xq], off offset:128\n" \
-    "global_load_dwordx2 v[120:121], %[xq], off offset:256\n" \
-    "global_load_dwordx2 v[122:123], %[xq], off offset:384\n" \
-    "global_load_dwordx2 v[124:125], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[126:127], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "global_load_dwordx2 v[128:129], %[xq], off\n" \
-    "global_load_dwordx2 v[130:131], %[xq], off offset:128\n" \
-    "global_load_dwordx2 v[132:133], %[xq], off offset:256\n" \
-    "global_load_dwordx2 v[134:135], %[xq], off offset:384\n" \
-    "global_load_dwordx2 v[136:137], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[138:139], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "global_load_dwordx2 v[140:141], %[xq], off\n" \
-    "global_load_dwordx2 v[142:143], %[xq], off offset:128\n" \
-    "global_load_dwordx2 v[144:145], %[xq], off offset:256\n" \
-    "global_load_dwordx2 v[146:147], %[xq], off offset:384\n" \
-    "global_load_dwordx2 v[148:149], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[150:151], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "s_cmp_eq_u32 %[n], 0\n" \
-    "s_cbranch_scc1 2f\n" \
-    "1:\n" \
-    "global_load_dwordx2 v[152:153], %[xq], off\n" \
-    "global_load_dwordx2 v[154:155], %[xq], off offset:128\n" \
-    "global_load_dwordx2 v[156:157], %[xq], off offset:256\n" \
-    "global_load_dwordx2 v[158:159], %[xq], off offset:384\n" \
-    "global_load_dwordx2 v[160:161], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[162:163], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "s_waitcnt vmcnt(18)\n" \
-    "v_mul_f64 v[164:165], v[124:125], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[126:127], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[116:117], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[116:117], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[118:119], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[118:119], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[120:121], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[120:121], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[122:123], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[122:123], v[166:167], %[a31]\n" \
-    "global_load_dwordx2 v[116:117], %[xq], off\n" \
-    "global_load_dwordx2 v[118:119], %[xq], off offset:128\n" \
-    "global_load_dwordx2 v[120:121], %[xq], off offset:256\n" \
-    "global_load_dwordx2 v[122:123], %[xq], off offset:384\n" \
-    "global_load_dwordx2 v[124:125], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[126:127], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "s_waitcnt vmcnt(18)\n" \
-    "v_mul_f64 v[164:165], v[136:137], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[138:139], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[128:129], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[128:129], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[130:131], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[130:131], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[132:133], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[132:133], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[134:135], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[134:135], v[166:167], %[a31]\n" \
-    "global_load_dwordx2 v[128:129], %[xq], off\n" \
-    "global_load_dwordx2 v[130:131], %[xq], off offset:128\n" \
-    "global_load_dwordx2 v[132:133], %[xq], off offset:256\n" \
-    "global_load_dwordx2 v[134:135], %[xq], off offset:384\n" \
-    "global_load_dwordx2 v[136:137], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[138:139], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "s_waitcnt vmcnt(18)\n" \
-    "v_mul_f64 v[164:165], v[148:149], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[150:151], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[140:141], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[140:141], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[142:143], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[142:143], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[144:145], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[144:145], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[146:147], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[146:147], v[166:167], %[a31]\n" \
-    "global_load_dwordx2 v[140:141], %[xq], off\n" \
-    "global_load_dwordx2 v[142:143], %[xq], off offset:128\n" \
-    "global_load_dwordx2 v[144:145], %[xq], off offset:256\n" \
-    "global_load_dwordx2 v[146:147], %[xq], off offset:384\n" \
-    "global_load_dwordx2 v[148:149], %[bo0], %[bb]\n" \
-    "global_load_dwordx2 v[150:151], %[bo1], %[bb]\n" \
-    "v_lshl_add_u64 %[xq], %[xq], 0, %[xs]\n" \
-    "v_add_u32 %[bo0], %[bs], %[bo0]\n" \
-    "v_add_u32 %[bo1], %[bs], %[bo1]\n" \
-    "s_waitcnt vmcnt(18)\n" \
-    "v_mul_f64 v[164:165], v[160:161], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[162:163], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[152:153], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[152:153], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[154:155], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[154:155], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[156:157], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[156:157], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[158:159], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[158:159], v[166:167], %[a31]\n" \
-    "s_sub_u32 %[n], %[n], 1\n" \
-    "s_cmp_lg_u32 %[n], 0\n" \
-    "s_cbranch_scc1 1b\n" \
-    "2:\n" \
-    "s_waitcnt vmcnt(12)\n" \
-    "v_mul_f64 v[164:165], v[124:125], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[126:127], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[116:117], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[116:117], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[118:119], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[118:119], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[120:121], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[120:121], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[122:123], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[122:123], v[166:167], %[a31]\n" \
-    "s_waitcnt vmcnt(6)\n" \
-    "v_mul_f64 v[164:165], v[136:137], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[138:139], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[128:129], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[128:129], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[130:131], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[130:131], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[132:133], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[132:133], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[134:135], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[134:135], v[166:167], %[a31]\n" \
-    "s_waitcnt vmcnt(0)\n" \
-    "v_mul_f64 v[164:165], v[148:149], %[q0]\n" \
-    "v_mul_f64 v[166:167], v[150:151], %[q1]\n" \
-    "s_nop 1\n" \
-    "v_mfma_f64_16x16x4_f64 %[a00], v[140:141], v[164:165], %[a00]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a01], v[140:141], v[166:167], %[a01]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a10], v[142:143], v[164:165], %[a10]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a11], v[142:143], v[166:167], %[a11]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a20], v[144:145], v[164:165], %[a20]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a21], v[144:145], v[166:167], %[a21]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a30], v[146:147], v[164:165], %[a30]\n" \
-    "v_mfma_f64_16x16x4_f64 %[a31], v[146:147], v[166:167], %[a31]\n" \
-    "s_nop 7\n" \
-    "s_nop 7\n" \
-    "s_nop 7\n"
-#define MTTKRP_PIPE_D42_CLOBBERS "v116", "v117", "v118", "v119", "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "v128", "v129", "v130", "v131", "v132", "v133", "v134", "v135", "v136", "v137", "v138", "v139", "v140", "v141", "v142", "v143", "v144", "v145", "v146", "v147", "v148", "v149", "v150", "v151", "v152", "v153", "v154", "v155", "v156", "v157", "v158", "v159", "v160", "v161", "v162", "v163", "v164", "v165", "v166", "v167", "scc", "memory"
+#include "mttkrp_pipe.inc"
 
 template <bool NT>
 __device__ __forceinline__ void pipelined_run_d42(double4_t (&acc)[4][2], const double*& xq,
                                                   int64_t x_step_bytes, const double* bbase,
-                                                  uint32_t bo0, uint32_t bo1, uint32_t b_step_bytes,
-                                                  double q0, double q1, int n_loop)
+                                                  uint32_t bo, uint32_t b_step_bytes,
+                                                  double q0, double q1, int n_loop, int rem)
 {
 #define MTTKRP_PIPE_D42_OPERANDS                                                                   \
-    [xq] "+v"(xq), [bo0] "+v"(bo0), [bo1] "+v"(bo1), [n] "+s"(n_loop), [a00] "+v"(acc[0][0]),      \
+    [xq] "+v"(xq), [bo] "+v"(bo), [n] "+s"(n_loop), [a00] "+v"(acc[0][0]),      \
         [a01] "+v"(acc[0][1]), [a10] "+v"(acc[1][0]), [a11] "+v"(acc[1][1]), [a20] "+v"(acc[2][0]), \
         [a21] "+v"(acc[2][1]), [a30] "+v"(acc[3][0]), [a31] "+v"(acc[3][1])                         \
-        : [xs] "s"(x_step_bytes), [bb] "s"(bbase), [bs] "s"(b_step_bytes), [q0] "v"(q0), [q1] "v"(q1) \
+        : [xs] "s"(x_step_bytes), [bb] "s"(bbase), [bs] "s"(b_step_bytes), [q0] "v"(q0), [q1] "v"(q1), \
+          [rem] "s"(rem)                                                                           \
         : MTTKRP_PIPE_D42_CLOBBERS
     if (NT)
         asm volatile(MTTKRP_PIPE_D42_ASM_NT : MTTKRP_PIPE_D42_OPERANDS);
@@ -428,12 +110,11 @@ template <> struct HasPipe<double, 4, 2> { static constexpr bool value = true; }
 // Generic stand-in so that the call below compiles for every instantiation.
 template <bool NT, typename T, int RB, int JB>
 __device__ __forceinline__ void pipelined_run(typename Mfma<T>::acc_t (&acc)[RB][JB], const T*& xq,
-                                              int64_t x_step_bytes, const T* bbase, uint32_t bo0,
-                                              uint32_t bo1, uint32_t b_step_bytes, T q0, T q1,
-                                              int n_loop)
+                                              int64_t x_step_bytes, const T* bbase, uint32_t bo,
+                                              uint32_t b_step_bytes, T q0, T q1, int n_loop, int rem)
 {
     if constexpr (HasPipe<T, RB, JB>::value)
-        pipelined_run_d42<NT>(acc, xq, x_step_bytes, bbase, bo0, bo1, b_step_bytes, q0, q1, n_loop);
+        pipelined_run_d42<NT>(acc, xq, x_step_bytes, bbase, bo, b_step_bytes, q0, q1, n_loop, rem);
 }
 
 template <typename T> struct StreamArgs {
@@ -459,8 +140,30 @@ template <typename T> struct StreamArgs {
     int32_t xcd_remap;
     int32_t group4;              // first mode: 1 = four wavefronts per partial tile (LDS sum)
     int32_t no_inner;            // 1: no column mode at all; A_in is only a readable dummy
+#ifdef MTTKRP_TRACE
+    long long* trace;            // debug builds: four clock readings per work item, or null
+#endif
 };
 
+
+// How the N 16-wide MFMA blocks of a wavefront tile map to rows (or output
+// columns).  A lane feeds MFMA index m of every block, so giving it N consecutive
+// rows lets one wide load instruction fetch its entries for all N blocks: block b
+// holds rows N*m + b.  A load instruction carries at most 16 bytes per lane, so
+// more than 16 bytes are split into two chunks of n0 and n1 blocks; chunk 0 covers
+// the first 16*n0 rows, chunk 1 the next 16*n1, and within each chunk every
+// 16-lane group still reads one contiguous piece of memory.
+template <typename T, int N> struct Lay {
+    static constexpr int G = 16 / (int)sizeof(T);
+    static constexpr int n0 = N < G ? N : G;
+    static constexpr int n1 = N - n0;
+    static_assert(n1 <= G, "at most two chunks");
+    // offset of block b's entry for MFMA index m from the tile's first row (column)
+    static __device__ __forceinline__ int off(int b, int m)
+    {
+        return b < n0 ? n0 * m + b : 16 * n0 + n1 * m + (b - n0);
+    }
+};
 
 // Load of a tensor entry.  When every 16-row segment a load instruction reads is
 // a whole, aligned 128-byte line (fp64, I_0 a multiple of 16, aligned X), the line
@@ -473,6 +176,46 @@ template <bool NT, typename T> __device__ __forceinline__ T stream_load(const T*
     if (NT)
         return __builtin_nontemporal_load(p);
     return *p;
+}
+
+// n consecutive values; the compiler merges them into one wide load instruction
+template <bool NT, int N, typename T> __device__ __forceinline__ void load_vec(const T* p, T* out)
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+        out[i] = stream_load<NT>(p + i);
+}
+// Rows use the same scheme in fp32 and for three fp64 row blocks.  With two or
+// four fp64 row blocks every row block keeps a load instruction of its own (block
+// b holds rows 16*b + m, 8 bytes per lane): measured on 1024- and 16384-row
+// tensors, 16-byte non-temporal tensor loads cost 3 to 15 % of the bandwidth there.
+template <typename T, int N> struct LayRows : Lay<T, N> {};
+#ifndef MTTKRP_F64_WIDE_ROWS
+#define MTTKRP_F64_WIDE_ROWS 0      // 1: 16-byte tensor loads for every fp64 tile (experiments)
+#endif
+#if !MTTKRP_F64_WIDE_ROWS
+template <> struct LayRows<double, 2> {
+    static constexpr int n0 = 1;
+    static constexpr int n1 = 0;
+    static __device__ __forceinline__ int off(int b, int m) { return 16 * b + m; }
+};
+template <> struct LayRows<double, 4> : LayRows<double, 2> {};
+#endif
+
+// the entries of one lane for all N row blocks; d1 = lane offset of chunk 1
+template <bool NT, int N, typename T>
+__device__ __forceinline__ void load_blocks(const T* p, int d1, T* out)
+{
+    typedef LayRows<T, N> L;
+    if constexpr (L::n0 == 1 && L::n1 == 0 && N > 1) {
+#pragma unroll
+        for (int b = 0; b < N; ++b)
+            out[b] = stream_load<NT>(p + 16 * b);
+    } else {
+        load_vec<NT, L::n0>(p, out);
+        if constexpr (L::n1 > 0)
+            load_vec<NT, L::n1>(p + d1, out + L::n0);
+    }
 }
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -525,6 +268,11 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
     // Other modes: one independent item per wavefront.
     const bool grouped = p.first_mode && p.group4;   // four wavefronts sum their tiles in LDS
     uint32_t it = grouped ? blk : blk * kWaves + wave;
+#ifdef MTTKRP_TRACE
+    const uint32_t trace_item = blk * kWaves + wave;
+    long long trace_t[4];
+    trace_t[0] = (long long)__builtin_readcyclecounter();
+#endif
     if (it >= (uint32_t)(grouped ? p.n_items / kWaves : p.n_items))
         return;
     const int rowblk = uni((int)(it % (uint32_t)p.n_rowblk));  it /= (uint32_t)p.n_rowblk;
@@ -536,7 +284,9 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
     const int osp = empty ? 0 : uni((int)(sp / (uint32_t)p.n_isplit));
     const int isp = empty ? 0 : uni((int)(sp - (uint32_t)osp * (uint32_t)p.n_isplit));
 
-    const int il = lane & 15;   // row inside a 16-row block (operand A) = column inside a 16-column block (B, D)
+    typedef LayRows<T, RB> LR;  // rows of the RB row blocks
+    typedef Lay<T, JB> LC;      // output columns of the JB column blocks
+    const int il = lane & 15;   // MFMA index of this lane: row index for operand A, column index for B and D
     const int kk = lane >> 4;   // which of the step's four columns this lane feeds
     const int R = p.R;
 
@@ -547,14 +297,30 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
     int row_base = first_row;
     if (row_base + 16 * RB > p.I0)
         row_base = p.I0 > 16 * RB ? p.I0 - 16 * RB : 0;
-    const int il_c = min(il, p.I0 - 1 - row_base);
+    const int lrow = min(LR::n0 * il, p.I0 - LR::n0 - row_base);        // this lane's first row in the tile (chunk 0)
+    const int xd1 = 16 * LR::n0 + (LR::n1 - LR::n0) * il;              // from there to its first row of chunk 1
 
-    // Columns of the output (j): clamp for loads, mask at the stores.
+    // Columns of the output (j).  A lane holds LC::n0 consecutive columns (and LC::n1 more of
+    // chunk 1).  Where such a group would cross R it is moved back to end at R, so that every
+    // load stays inside the factor rows; the columns it then shares with a lower lane are
+    // computed twice and stored by their owner only.
     const int j_first = jchunk * (16 * JB);
-    int jc[JB];
+    const int jt0 = j_first + LC::n0 * il;
+    const int jt1 = j_first + 16 * LC::n0 + LC::n1 * il;
+    const int js0 = min(jt0, R - LC::n0);
+    const int js1 = LC::n1 > 0 ? min(jt1, R - LC::n1) : 0;
+    int jc[JB];          // column of block jb in this lane
+    bool jown[JB];       // and whether this lane stores it
 #pragma unroll
-    for (int jb = 0; jb < JB; ++jb)
-        jc[jb] = min(j_first + 16 * jb + il, R - 1);
+    for (int jb = 0; jb < JB; ++jb) {
+        jc[jb] = jb < LC::n0 ? js0 + jb : js1 + (jb - LC::n0);
+        jown[jb] = jb < LC::n0 ? jc[jb] >= jt0 : jc[jb] >= jt1;
+    }
+    auto load_cols = [&](const T* row, T (&out)[JB]) {     // entries of a factor row at this lane's columns
+        load_vec<false, LC::n0>(row + js0, out);
+        if constexpr (LC::n1 > 0)
+            load_vec<false, LC::n1>(row + js1, out + LC::n0);
+    };
 
     // Range of this item in the (outer iteration, inner column) space.
     const int ia_begin = isp * p.cols_per_isplit;
@@ -563,7 +329,7 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
     const int64_t o_begin = (int64_t)osp * p.o_per_item;
     const int o_count = empty ? 0 : uni((int)min(p.o_per_item, p.o_total - o_begin));
 
-    const T* const xlane = p.X + (int64_t)batch * p.sx_batch + (row_base + il_c);
+    const T* const xlane = p.X + (int64_t)batch * p.sx_batch + (row_base + lrow);
     const int64_t x_step = 4 * p.sx_in;
     const bool no_inner = p.no_inner != 0;   // then A_in is a readable dummy and b = 1
     const int dim_mid = p.dim_out[0];        // 1 when there is no outer mode
@@ -592,18 +358,20 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
 #pragma unroll
         for (int m = 1; m < kMaxOuter; ++m) {
             if (m < p.n_out) {
-                const T* a = p.A_out[m] + (int64_t)i_far[m] * R;
+                T a[JB];
+                load_cols(p.A_out[m] + (int64_t)i_far[m] * R, a);
 #pragma unroll
                 for (int jb = 0; jb < JB; ++jb)
-                    Qfar[jb] *= a[jc[jb]];
+                    Qfar[jb] *= a[jb];
             }
         }
     };
     auto load_Q = [&]() {         // Q of the sweep the cursor enters
-        const T* a = A_mid + (int64_t)(has_mid ? i_mid : 0) * R;
+        T a[JB];
+        load_cols(A_mid + (int64_t)(has_mid ? i_mid : 0) * R, a);
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
-            Q[jb] = has_mid ? Qfar[jb] * a[jc[jb]] : Qfar[jb];
+            Q[jb] = has_mid ? Qfar[jb] * a[jb] : Qfar[jb];
     };
 #pragma unroll
     for (int m = 0; m < kMaxOuter; ++m)
@@ -629,10 +397,14 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
     int s_in = 0;                       // step inside the current sweep
     const T* xp = xlane + xoff_far + (int64_t)i_mid * sx_mid + (int64_t)(ia_begin + kk) * p.sx_in;
     const T* bbase = p.A_in + (int64_t)ia_begin * R;            // wave-uniform: factor row of the step's first column
-    uint32_t boff[JB];                                          // per-lane byte offset of (column kk, output column j)
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb)
-        boff[jb] = ((uint32_t)kk * (uint32_t)R + (uint32_t)jc[jb]) * (uint32_t)sizeof(T);
+    // per-lane byte offsets of (column kk, first output column of chunk 0 / chunk 1)
+    const uint32_t boff0 = ((uint32_t)kk * (uint32_t)R + (uint32_t)js0) * (uint32_t)sizeof(T);
+    const uint32_t boff1 = ((uint32_t)kk * (uint32_t)R + (uint32_t)js1) * (uint32_t)sizeof(T);
+    auto load_b = [&](const char* row, T (&out)[JB]) {      // factor entries of one step
+        load_vec<false, LC::n0>((const T*)(row + boff0), out);
+        if constexpr (LC::n1 > 0)
+            load_vec<false, LC::n1>((const T*)(row + boff1), out + LC::n0);
+    };
     const int n_steps = o_count * steps_in;   // < 2^30, checked on the host
     int remaining = n_steps;        // steps not yet issued, the cursor's included
     bool parked = false;                // all steps issued: the cursor stays on the last one, weight 0
@@ -670,12 +442,13 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
         const bool last = s_in == steps_in - 1;           // wave-uniform
         const T* xe = last ? xp - x_back : xp;
         const char* be = (const char*)(last ? bbase - b_back : bbase);
+        load_blocks<NT, RB>(xe, xd1, xn);
+        load_b(be, bn);
+        if (no_inner) {
 #pragma unroll
-        for (int r = 0; r < RB; ++r)
-            xn[r] = stream_load<NT>(xe + 16 * r);
-#pragma unroll
-        for (int jb = 0; jb < JB; ++jb)
-            bn[jb] = no_inner ? (T)1 : *(const T*)(be + boff[jb]);
+            for (int jb = 0; jb < JB; ++jb)
+                bn[jb] = (T)1;
+        }
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
             qn[jb] = (parked || (last && !lane_ok)) ? (T)0 : Q[jb];
@@ -709,18 +482,22 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
     // Other wavefronts of the SIMD fill the gaps between batches.
     //   plain batch:   U unmasked steps of one sweep: one weight Q, constant strides
     //   generic batch: any steps (sweep boundaries, masked last step, parked padding)
+#ifdef MTTKRP_TRACE
+    trace_t[1] = (long long)__builtin_readcyclecounter();
+#endif
     // the pipelined run addresses the inner factor with 32-bit offsets
     const bool pipe_ok = HasPipe<T, RB, JB>::value && (int64_t)p.I_in * R * (int64_t)sizeof(T) < ((int64_t)1 << 31);
     int done = 0;
     while (done < n_steps) {
         if (HasPipe<T, RB, JB>::value) {
             const int avail = parked || !pipe_ok ? 0 : min(remaining, steps_plain - s_in);
-            if (avail >= 7) {
-                const int n_loop = (avail - 3) >> 2;
-                const int n_run = 3 + 4 * n_loop;
-                pipelined_run<NT, T, RB, JB>(acc, xp, x_step * (int64_t)sizeof(T), bbase, boff[0],
-                                             boff[JB > 1 ? 1 : 0], 4u * (uint32_t)R * (uint32_t)sizeof(T),
-                                             Q[0], Q[JB > 1 ? 1 : 0], n_loop);
+            if (avail >= MTTKRP_PIPE_D42_DEPTH) {
+                const int n_loop = (avail - MTTKRP_PIPE_D42_DEPTH) / MTTKRP_PIPE_D42_RING;
+                const int n_run = avail;
+                const int rem = avail - MTTKRP_PIPE_D42_DEPTH - n_loop * MTTKRP_PIPE_D42_RING;
+                pipelined_run<NT, T, RB, JB>(acc, xp, x_step * (int64_t)sizeof(T), bbase, boff0,
+                                             4u * (uint32_t)R * (uint32_t)sizeof(T),
+                                             Q[0], Q[JB > 1 ? 1 : 0], n_loop, rem);
                 bbase += (int64_t)n_run * 4 * R;
                 s_in += n_run;
                 remaining -= n_run;
@@ -743,14 +520,11 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
             const char* bu = (const char*)bbase;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                load_blocks<NT, RB>(xu, xd1, xs[u]);
+                load_b(bu, bs[u]);
 #pragma unroll
-                for (int r = 0; r < RB; ++r)
-                    xs[u][r] = stream_load<NT>(xu + 16 * r);
-#pragma unroll
-                for (int jb = 0; jb < JB; ++jb) {
-                    bs[u][jb] = *(const T*)(bu + boff[jb]);
+                for (int jb = 0; jb < JB; ++jb)
                     qs[u][jb] = Q[jb];
-                }
                 xu += x_step;
                 bu += 4 * (int64_t)R * (int64_t)sizeof(T);
             }
@@ -788,6 +562,9 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
         }
     }
 
+#ifdef MTTKRP_TRACE
+    trace_t[2] = (long long)__builtin_readcyclecounter();
+#endif
     // Epilogue.
     if (p.first_mode && !grouped) {
         T* o = p.out + (int64_t)group * ((int64_t)p.I0 * R);
@@ -797,10 +574,9 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
             for (int jb = 0; jb < JB; ++jb)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int row = row_base + 16 * r + MF::row(lane, q);
-                    const int j = j_first + 16 * jb + il;
-                    if (row >= first_row && row < p.I0 && j < R)
-                        o[(int64_t)row * R + j] = acc[r][jb][q];
+                    const int row = row_base + LR::off(r, MF::row(lane, q));
+                    if (row >= first_row && row < p.I0 && jown[jb])
+                        o[(int64_t)row * R + jc[jb]] = acc[r][jb][q];
                 }
     } else if (p.first_mode) {
         // Sum the four wavefronts' tiles in LDS in a fixed order, (w0 + w2) + (w1 + w3);
@@ -851,35 +627,72 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const T v = acc[r][jb][q] + src[((r * JB + jb) * 4 + q) * 64];
-                        const int row = row_base + 16 * r + MF::row(lane, q);
-                        const int j = j_first + 16 * jb + il;
-                        if (row >= first_row && row < p.I0 && j < R)
-                            o[(int64_t)row * R + j] = v;
+                        const int row = row_base + LR::off(r, MF::row(lane, q));
+                        if (row >= first_row && row < p.I0 && jown[jb])
+                            o[(int64_t)row * R + jc[jb]] = v;
                     }
         }
     } else {
         const int64_t slot = ((int64_t)osp * p.n_isplit + isp) * p.n_rowblk + rowblk;
         T* o = p.out + ((int64_t)batch * p.n_slots + slot) * R;
+        // Weighted sum over the tile's rows: M(i_k, j) += sum_r A_0(r, j) T(r, j).  The weights
+        // of a group of row blocks are all loaded before any is used (one round trip to L2 per
+        // group); rows this item does not own (overlap of the shifted last block) get weight 0.
+        constexpr int RG = 64 / (4 * JB * (int)(sizeof(T) / 4)) < 1 ? 1 : 64 / (4 * JB * (int)(sizeof(T) / 4));
+        double v[JB];
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb)
+            v[jb] = 0.0;
+#pragma unroll
+        for (int r0 = 0; r0 < RB; r0 += RG) {
+            T w[RG][4][JB];
+#pragma unroll
+            for (int rr = 0; rr < RG; ++rr)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (r0 + rr < RB) {
+                        const int row = row_base + LR::off(r0 + rr, MF::row(lane, q));
+                        load_cols(p.A_row + (int64_t)min(row, p.I0 - 1) * R, w[rr][q]);
+                    }
+#pragma unroll
+            for (int rr = 0; rr < RG; ++rr)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int jb = 0; jb < JB; ++jb)
+                        if (r0 + rr < RB)
+                            asm volatile("" : "+v"(w[rr][q][jb]));   // keeps the loads unconditional and ahead of the sums
+#pragma unroll
+            for (int rr = 0; rr < RG; ++rr)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (r0 + rr < RB) {
+                        const int row = row_base + LR::off(r0 + rr, MF::row(lane, q));
+                        const bool ok = row >= first_row && row < p.I0;
+#pragma unroll
+                        for (int jb = 0; jb < JB; ++jb) {
+                            const double t = (double)acc[r0 + rr][jb][q] * (double)w[rr][q][jb];
+                            v[jb] += ok ? t : 0.0;
+                        }
+                    }
+        }
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb) {
-            double v = 0.0;
-#pragma unroll
-            for (int r = 0; r < RB; ++r)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int row = row_base + 16 * r + MF::row(lane, q);
-                    const bool ok = row >= first_row && row < p.I0;
-                    const int row_c = min(row, p.I0 - 1);
-                    const T w = p.A_row[(int64_t)row_c * R + jc[jb]];
-                    v += ok ? (double)acc[r][jb][q] * (double)w : 0.0;
-                }
-            v += __shfl_xor(v, 16);
-            v += __shfl_xor(v, 32);
-            const int j = j_first + 16 * jb + il;
-            if (kk == 0 && j < R)
-                o[j] = (T)v;
+            double t = v[jb];
+            t += __shfl_xor(t, 16);
+            t += __shfl_xor(t, 32);
+            if (kk == 0 && jown[jb])
+                o[jc[jb]] = (T)t;
         }
     }
+#ifdef MTTKRP_TRACE
+    trace_t[3] = (long long)__builtin_readcyclecounter();
+    if (p.trace && lane == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            p.trace[(int64_t)trace_item * 4 + i] = trace_t[i];
+    }
+#endif
 }
 
 // M(n, j) = sum of the partial sums of all slots, in fp64 and in a fixed order:
@@ -942,6 +755,11 @@ struct Tuning {
     int64_t ws_percent = 0;
     int64_t max_col_blocks = 0;
     int64_t first_group = 0;
+    int64_t waves_per_simd = 0;
+    int64_t nt_loads = 0;
+#ifdef MTTKRP_TRACE
+    int64_t trace_ptr = 0;      // debug builds: device buffer of 4 * n_items int64 clock readings
+#endif
 };
 Tuning g_tune;
 std::mutex g_mutex;
@@ -965,6 +783,8 @@ struct Plan {
     size_t ws_bytes = 0;
     bool xcd_remap = true;
     int group = 4;             // first mode: wavefronts per partial tile
+    int wave_cap = 0;          // > 0: resident wavefronts per SIMD are capped (by reserving LDS)
+    bool nt_off = false;       // never use non-temporal tensor loads
 };
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -1149,16 +969,25 @@ int make_plan(int ndim, const int64_t* dims, int R, int k, int sbytes, Plan& pl)
     pl.ws_bytes = pl.n_slots > 1
         ? (size_t)pl.n_slots * (size_t)dims[k] * (size_t)R * (size_t)sbytes : 0;
     pl.xcd_remap = tn.xcd_remap == 1;
+    pl.wave_cap = (int)tn.waves_per_simd;
+    pl.nt_off = tn.nt_loads == 1;
     return MTTKRP_OK;
 }
 
 template <typename T, int RB, int JB>
-void launch_stream(const StreamArgs<T>& a, dim3 grid, hipStream_t st)
+void launch_stream(const StreamArgs<T>& a, dim3 grid, hipStream_t st, int cap, bool nt_off)
 {
     // first mode: two wavefront tiles of LDS for the cross-wavefront sum
-    const size_t lds = a.first_mode && a.group4 ? (size_t)2 * RB * JB * 4 * 64 * sizeof(T) : 0;
+    size_t lds = a.first_mode && a.group4 ? (size_t)2 * RB * JB * 4 * 64 * sizeof(T) : 0;
+    // Resident wavefronts per SIMD can be capped by reserving LDS: a workgroup is one
+    // wavefront per SIMD, and a compute unit has 160 KB of LDS.
+    if (cap >= 1 && cap <= 7) {
+        const size_t want = (size_t)160 * 1024 / (size_t)(cap + 1) + 256;
+        if (want <= 65536 && want > lds)
+            lds = want;
+    }
     // non-temporal tensor loads only when each load instruction reads whole aligned lines
-    const bool nt = sizeof(T) == 8 && a.I0 % 16 == 0 && ((uintptr_t)a.X & 127u) == 0;
+    const bool nt = !nt_off && sizeof(T) == 8 && a.I0 % 16 == 0 && ((uintptr_t)a.X & 127u) == 0;
     if (nt)
         hipLaunchKernelGGL((mttkrp_stream_kernel<T, RB, JB, true>), grid, dim3(kBlockThreads), lds, st, a);
     else
@@ -1166,24 +995,24 @@ void launch_stream(const StreamArgs<T>& a, dim3 grid, hipStream_t st)
 }
 
 template <typename T, int RB>
-void launch_stream_jb(int JB, const StreamArgs<T>& a, dim3 grid, hipStream_t st)
+void launch_stream_jb(int JB, const StreamArgs<T>& a, dim3 grid, hipStream_t st, int cap, bool nt_off)
 {
     switch (JB) {
-    case 1: launch_stream<T, RB, 1>(a, grid, st); break;
-    case 2: launch_stream<T, RB, 2>(a, grid, st); break;
-    case 3: launch_stream<T, RB, 3>(a, grid, st); break;
-    default: launch_stream<T, RB, 4>(a, grid, st); break;
+    case 1: launch_stream<T, RB, 1>(a, grid, st, cap, nt_off); break;
+    case 2: launch_stream<T, RB, 2>(a, grid, st, cap, nt_off); break;
+    case 3: launch_stream<T, RB, 3>(a, grid, st, cap, nt_off); break;
+    default: launch_stream<T, RB, 4>(a, grid, st, cap, nt_off); break;
     }
 }
 
 template <typename T>
-void launch_stream_rb(int RB, int JB, const StreamArgs<T>& a, dim3 grid, hipStream_t st)
+void launch_stream_rb(int RB, int JB, const StreamArgs<T>& a, dim3 grid, hipStream_t st, int cap, bool nt_off)
 {
     switch (RB) {
-    case 1: launch_stream_jb<T, 1>(JB, a, grid, st); break;
-    case 2: launch_stream_jb<T, 2>(JB, a, grid, st); break;
-    case 3: launch_stream_jb<T, 3>(JB, a, grid, st); break;
-    default: launch_stream_jb<T, 4>(JB, a, grid, st); break;
+    case 1: launch_stream_jb<T, 1>(JB, a, grid, st, cap, nt_off); break;
+    case 2: launch_stream_jb<T, 2>(JB, a, grid, st, cap, nt_off); break;
+    case 3: launch_stream_jb<T, 3>(JB, a, grid, st, cap, nt_off); break;
+    default: launch_stream_jb<T, 4>(JB, a, grid, st, cap, nt_off); break;
     }
 }
 
@@ -1311,6 +1140,9 @@ int run(int ndim, const int64_t* dims, const T* X, const T* const* factors, int 
     a.n_splits = (int32_t)pl.n_splits;
     a.xcd_remap = pl.xcd_remap ? 1 : 0;
     a.group4 = pl.group == kWaves ? 1 : 0;
+#ifdef MTTKRP_TRACE
+    a.trace = (long long*)(uintptr_t)g_tune.trace_ptr;   // g_mutex is held here
+#endif
 
     int64_t blocks = ceil_div(pl.n_items, kWaves);
     if (a.xcd_remap)
@@ -1321,7 +1153,7 @@ int run(int ndim, const int64_t* dims, const T* X, const T* const* factors, int 
     (void)hipGetLastError();
     if (timing)
         (void)hipEventRecord(tc->ev[0], st);
-    launch_stream_rb<T>(pl.RB, pl.JB, a, dim3((unsigned)blocks), st);
+    launch_stream_rb<T>(pl.RB, pl.JB, a, dim3((unsigned)blocks), st, pl.wave_cap, pl.nt_off);
     if (timing) {
         (void)hipEventRecord(tc->ev[1], st);
         tc->combine = false;
@@ -1522,6 +1354,16 @@ int mttkrp_tune_set(const char* key, int64_t value)
     } else if (!strcmp(key, "first_group")) {
         if (value != 0 && value != 1 && value != 4) return MTTKRP_ERR_INVALID_ARG;
         g_tune.first_group = value;
+    } else if (!strcmp(key, "waves_per_simd")) {
+        if (value > 8) return MTTKRP_ERR_INVALID_ARG;
+        g_tune.waves_per_simd = value;
+#ifdef MTTKRP_TRACE
+    } else if (!strcmp(key, "trace_ptr")) {
+        g_tune.trace_ptr = value;
+#endif
+    } else if (!strcmp(key, "nt_loads")) {
+        if (value > 1) return MTTKRP_ERR_INVALID_ARG;
+        g_tune.nt_loads = value;
     } else if (!strcmp(key, "ws_percent")) {
         if (value > 100) return MTTKRP_ERR_INVALID_ARG;
         g_tune.ws_percent = value;
