@@ -253,7 +253,9 @@ template <typename T, int RB, int JB, bool NT>
 __global__ void __launch_bounds__(kBlockThreads, (Budget<T, RB, JB>::waves))
 mttkrp_stream_kernel(const StreamArgs<T> p)
 {
-    constexpr int U = Budget<T, RB, JB>::steps;   // steps per batch = steps of loads in flight
+    // steps per batch = steps of loads in flight; where the hand-scheduled run takes the bulk
+    // of the steps, short batches leave the registers to it
+    constexpr int U = HasPipe<T, RB, JB>::value ? 2 : Budget<T, RB, JB>::steps;
     typedef Mfma<T> MF;
     typedef typename MF::acc_t acc_t;
 
