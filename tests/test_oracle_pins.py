@@ -395,3 +395,44 @@ def test_lambda_is_a_column_scaling(oracle):
                 H = H * (U[m].T @ A[m])
         ref = (U[k] * mu) @ H * lam
         assert oracle.normwise_rel_err(oracle.mttkrp(Xk, A, k, lam=lam), ref) <= 1e-13
+
+
+# ---------------------------------------------------------------- tile-volume heuristic
+def _heuristic_cases():
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_tile_heuristic.txt")
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        f = [t.strip() for t in line.split("|")]
+        yield f[0], [int(t) for t in f[1].split()], int(f[2]), int(f[3]), int(f[4]), int(f[5]), int(f[6])
+
+
+def test_tile_heuristic_matches_the_papers_values():
+    """Eq. (heuristic) against the tile sizes the paper reports (Sec. IV-C)."""
+    from oracle import tile_heuristic
+    n = 0
+    for label, dims, cache, vb, c, width, vol in _heuristic_cases():
+        assert tile_heuristic.tile_volume(dims, cache, vb, c) == (width, vol), label
+        n += 1
+    assert n == 4
+
+
+def test_tile_heuristic_properties():
+    """The width is the integer (d-1)-th root of the budget, capped by the smallest extent."""
+    from oracle import tile_heuristic
+    import math
+    for d in (2, 3, 4, 5, 6):
+        for cache in (16384, 32768, 65536, 262144, 1 << 21):
+            for vb in (4, 8):
+                for c in (1, 2, 8, 64):
+                    dims = [10 ** 9] * d
+                    w, vol = tile_heuristic.tile_volume(dims, cache, vb, c)
+                    budget = cache / 4 / (vb * c / 2)
+                    assert vol == w ** (d - 1)
+                    assert w == 1 or w ** (d - 1) <= budget
+                    assert (w + 1) ** (d - 1) > budget
+                    assert abs(w - math.floor(budget ** (1.0 / (d - 1)) + 1e-9)) <= 1
+                    # cap by the smallest extent
+                    w2, vol2 = tile_heuristic.tile_volume([10 ** 9] * (d - 1) + [3], cache, vb, c)
+                    assert w2 == min(w, 3) and vol2 == w2 ** (d - 1)
