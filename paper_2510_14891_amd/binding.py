@@ -31,7 +31,12 @@ EXPORTED = (
     "mttkrp_version", "mttkrp_release", "mttkrp_timing_enable",
     "mttkrp_timing_count", "mttkrp_timing_get", "mttkrp_timing_last",
     "mttkrp_tune_set", "mttkrp_plan_describe",
+    "mttkrp_ablation_f64", "mttkrp_ablation_f32", "mttkrp_tile_volume",
 )
+
+MTTKRP_SCHEDULE_ELEM = 1
+MTTKRP_SCHEDULE_SUB = 2
+MTTKRP_SCHEDULE_TILE = 3
 
 _lib = None
 
@@ -93,6 +98,14 @@ def lib() -> ctypes.CDLL:
     L.mttkrp_plan_describe.restype = ctypes.c_int
     L.mttkrp_plan_describe.argtypes = [ctypes.c_int, i64p, ctypes.c_int, ctypes.c_int,
                                        ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
+    abl = [ctypes.c_int, ctypes.c_int, i64p, ctypes.c_void_p, vpp, ctypes.c_int, ctypes.c_int,
+           ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+    for name in ("mttkrp_ablation_f64", "mttkrp_ablation_f32"):
+        getattr(L, name).restype = ctypes.c_int
+        getattr(L, name).argtypes = abl
+    L.mttkrp_tile_volume.restype = ctypes.c_int
+    L.mttkrp_tile_volume.argtypes = [ctypes.c_int, i64p, ctypes.c_int64, ctypes.c_int, ctypes.c_int64,
+                                     i64p, i64p]
     _lib = L
     return L
 
@@ -167,27 +180,10 @@ def mttkrp_dense_ex_workspace_bytes(dims: Sequence[int], R: int, k: int, dtype_b
     return int(n)
 
 
-def mttkrp_dense(X, dims: Sequence[int], factors: Sequence, k: int, M=None,
-                 workspace=None, stream: Optional[int] = None, lam=None, beta=None):
-    """M = X_(k) (Khatri-Rao of all factors but the k-th), on the GPU.
-
-    X        flat torch tensor on a HIP device, prod(dims) values, first index
-             fastest; float64 or float32
-    dims     extents (I_0, ..., I_{d-1})
-    factors  d torch tensors, factors[m] of shape (I_m, R), contiguous, same
-             dtype/device as X; factors[k] may be None
-    k        0-based mode
-    M        optional output tensor (I_k, R); allocated when None
-    workspace  optional torch tensor to use as caller-owned workspace (selects
-             the *_ws entry point)
-    lam, beta  optional weight vector (torch tensor of R values on the device)
-             and accumulation factor; either selects the *_ex entry point:
-             M = beta * M + result * diag(lam)
-    stream   raw hipStream_t value; default: torch's current stream
-    Returns M.  The call is asynchronous on the stream.
-    """
+def _marshal(X, dims, factors, k, M, stream):
+    """Checks the tensors of one call and returns (suffix, d, factor pointer
+    array, R, M, stream) ready for the C entry points."""
     import torch
-    L = lib()
     if not X.is_cuda:
         raise ValueError("X must live on the GPU")
     if X.dtype == torch.float64:
@@ -232,6 +228,31 @@ def mttkrp_dense(X, dims: Sequence[int], factors: Sequence, k: int, M=None,
             raise ValueError("M must be a contiguous (I_k, R) tensor like X")
     if stream is None:
         stream = torch.cuda.current_stream(X.device).cuda_stream
+    return suffix, d, ptrs, R, M, stream
+
+
+def mttkrp_dense(X, dims: Sequence[int], factors: Sequence, k: int, M=None,
+                 workspace=None, stream: Optional[int] = None, lam=None, beta=None):
+    """M = X_(k) (Khatri-Rao of all factors but the k-th), on the GPU.
+
+    X        flat torch tensor on a HIP device, prod(dims) values, first index
+             fastest; float64 or float32
+    dims     extents (I_0, ..., I_{d-1})
+    factors  d torch tensors, factors[m] of shape (I_m, R), contiguous, same
+             dtype/device as X; factors[k] may be None
+    k        0-based mode
+    M        optional output tensor (I_k, R); allocated when None
+    workspace  optional torch tensor to use as caller-owned workspace (selects
+             the *_ws entry point)
+    lam, beta  optional weight vector (torch tensor of R values on the device)
+             and accumulation factor; either selects the *_ex entry point:
+             M = beta * M + result * diag(lam)
+    stream   raw hipStream_t value; default: torch's current stream
+    Returns M.  The call is asynchronous on the stream.
+    """
+    import torch
+    L = lib()
+    suffix, d, ptrs, R, M, stream = _marshal(X, dims, factors, k, M, stream)
     if lam is not None and (lam.dtype != X.dtype or lam.device != X.device
                             or not lam.is_contiguous() or lam.numel() != R):
         raise ValueError("lam must be a contiguous device vector of R values like X")
@@ -255,3 +276,28 @@ def mttkrp_dense(X, dims: Sequence[int], factors: Sequence, k: int, M=None,
                 ctypes.c_void_p(stream))
     _check(rc)
     return M
+
+
+def mttkrp_ablation(schedule: int, X, dims: Sequence[int], factors: Sequence, k: int,
+                    tile_width: int = 0, M=None, stream: Optional[int] = None):
+    """The same M by one of the paper's own schedules (ELEM, SUB, TILE); see
+    include/mttkrp_ablation.h.  Arguments as for mttkrp_dense; ``tile_width``
+    is the TILE schedule's entries per tile along each mode other than k."""
+    import torch
+    L = lib()
+    suffix, d, ptrs, R, M, stream = _marshal(X, dims, factors, k, M, stream)
+    with torch.cuda.device(X.device):
+        rc = getattr(L, "mttkrp_ablation_" + suffix)(
+            int(schedule), d, _dims_array(dims), X.data_ptr(), ptrs, R, int(k), int(tile_width),
+            M.data_ptr(), ctypes.c_void_p(stream))
+    _check(rc)
+    return M
+
+
+def mttkrp_tile_volume(dims: Sequence[int], cache_bytes: int, value_bytes: int,
+                       tiles_per_unit: int):
+    """(width, N_T) of the paper's tile-volume heuristic; host arithmetic only."""
+    w, v = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(lib().mttkrp_tile_volume(len(dims), _dims_array(dims), int(cache_bytes), int(value_bytes),
+                                    int(tiles_per_unit), ctypes.byref(w), ctypes.byref(v)))
+    return int(w.value), int(v.value)

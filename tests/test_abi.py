@@ -8,7 +8,8 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "mttkrp.h")
+HEADERS = [os.path.join(ROOT, "include", n) for n in sorted(os.listdir(os.path.join(ROOT, "include")))
+           if n.endswith(".h")]
 
 
 @pytest.fixture(scope="module")
@@ -21,9 +22,12 @@ def mt():
 
 
 def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(mttkrp_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in HEADERS:
+        text = open(header).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(mttkrp_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_symbols_are_exported(mt):
@@ -79,3 +83,26 @@ def test_workspace_stays_in_the_sum_of_dims_class(mt):
             slots = int(re.search(r"slots=(\d+)", desc).group(1))
             assert ws == (slots * w.dims[k] * w.R * w.itemsize if slots > 1 else 0)
             assert slots <= 4096, (name, k, slots)
+
+
+def test_tile_volume_matches_the_oracle(mt):
+    """Eq. (heuristic): the library's integer arithmetic against the oracle's exact
+    rational arithmetic, value for value (host only)."""
+    from oracle import tile_heuristic
+    shapes = [(401, 201, 12, 501), (129, 129, 129, 12, 39), (1024, 1024, 512), (7, 5), (3, 1, 2, 2),
+              (48,) * 5, (192,) * 4, (2, 2, 2, 2, 2, 2, 2, 2)]
+    n = 0
+    for dims in shapes:
+        for cache in (1, 100, 16384, 32768, 65536, 163840, 262144, 1 << 21, (1 << 22) + 5):
+            for vb in (4, 8):
+                for c in (1, 2, 3, 8, 32, 64, 1000):
+                    assert mt.mttkrp_tile_volume(dims, cache, vb, c) == \
+                        tile_heuristic.tile_volume(dims, cache, vb, c), (dims, cache, vb, c)
+                    n += 1
+    assert n > 1000
+    L = mt.lib()
+    w = ctypes.c_int64(0)
+    d3 = (ctypes.c_int64 * 3)(4, 4, 4)
+    assert L.mttkrp_tile_volume(3, d3, 0, 8, 1, ctypes.byref(w), ctypes.byref(w)) == mt.MTTKRP_ERR_INVALID_ARG
+    assert L.mttkrp_tile_volume(1, d3, 1024, 8, 1, ctypes.byref(w), ctypes.byref(w)) == mt.MTTKRP_ERR_INVALID_ARG
+    assert L.mttkrp_ablation_f64(9, 3, d3, None, None, 4, 0, 1, None, None) == mt.MTTKRP_ERR_INVALID_ARG
