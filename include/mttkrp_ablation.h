@@ -54,8 +54,8 @@ typedef enum {
  *   overwritten (the library clears it first where the schedule accumulates
  *   with atomics).  No workspace is used.
  * Returns an mttkrp_status; MTTKRP_ERR_INVALID_ARG also for an unknown
- * schedule or tile_width < 1 with TILE; MTTKRP_ERR_UNSUPPORTED when the number
- * of tiles or entries does not fit the launch limits (>= 2^31 workgroups).
+ * schedule or tile_width < 1 with TILE; MTTKRP_ERR_UNSUPPORTED when a subtensor
+ * would hold 2^40 tiles or more.
  */
 int mttkrp_ablation_f64(int schedule, int ndim, const int64_t* dims, const double* X,
                         const double* const* factors, int R, int k, int64_t tile_width,

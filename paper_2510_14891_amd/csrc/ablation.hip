@@ -51,33 +51,33 @@ template <typename T> __global__ void __launch_bounds__(kTeamThreads) elem_kerne
     const int bx = kTeamThreads / p.by;
     const int px = (int)threadIdx.x / p.by;
     const int py = (int)threadIdx.x - px * p.by;
-    const int64_t i = (int64_t)blockIdx.x * bx + px;
-    if (i >= p.n_units)
-        return;
-    const T y = p.X[i];
-    int64_t idx[MTTKRP_MAX_NDIM];
-    int64_t rem = i;
+    // a launch holds at most 2^32 threads, so team threads stride over the entries
+    for (int64_t i = (int64_t)blockIdx.x * bx + px; i < p.n_units; i += (int64_t)gridDim.x * bx) {
+        const T y = p.X[i];
+        int64_t idx[MTTKRP_MAX_NDIM];
+        int64_t rem = i;
 #pragma unroll
-    for (int m = 0; m < MTTKRP_MAX_NDIM; ++m) {
-        idx[m] = 0;
-        if (m < p.ndim) {
-            const int64_t q = rem / p.dims[m];
-            idx[m] = rem - q * p.dims[m];
-            rem = q;
+        for (int m = 0; m < MTTKRP_MAX_NDIM; ++m) {
+            idx[m] = 0;
+            if (m < p.ndim) {
+                const int64_t q = rem / p.dims[m];
+                idx[m] = rem - q * p.dims[m];
+                rem = q;
+            }
         }
-    }
-    int64_t ik = 0;
-#pragma unroll
-    for (int m = 0; m < MTTKRP_MAX_NDIM; ++m)
-        if (m == p.k)
-            ik = idx[m];
-    for (int j = py; j < p.R; j += p.by) {
-        T phi = y;
+        int64_t ik = 0;
 #pragma unroll
         for (int m = 0; m < MTTKRP_MAX_NDIM; ++m)
-            if (m < p.ndim && m != p.k)
-                phi *= p.A[m][idx[m] * p.R + j];
-        atomic_add(&p.M[ik * p.R + j], phi);
+            if (m == p.k)
+                ik = idx[m];
+        for (int j = py; j < p.R; j += p.by) {
+            T phi = y;
+#pragma unroll
+            for (int m = 0; m < MTTKRP_MAX_NDIM; ++m)
+                if (m < p.ndim && m != p.k)
+                    phi *= p.A[m][idx[m] * p.R + j];
+            atomic_add(&p.M[ik * p.R + j], phi);
+        }
     }
 }
 
@@ -92,64 +92,64 @@ template <typename T> __global__ void __launch_bounds__(kTeamThreads) tile_kerne
     const int bx = kTeamThreads / p.by;
     const int px = (int)threadIdx.x / p.by;
     const int py = (int)threadIdx.x - px * p.by;
-    const int64_t u = (int64_t)blockIdx.x * bx + px;
-    if (u >= p.n_units)
-        return;
-    const int64_t n = u / p.tiles_per_sub;
-    int64_t t = u - n * p.tiles_per_sub;
-    int64_t a[MTTKRP_MAX_NDIM], len[MTTKRP_MAX_NDIM];
-    int64_t base = 0, vol = 1;
+    // a launch holds at most 2^32 threads, so team threads stride over the tiles
+    for (int64_t u = (int64_t)blockIdx.x * bx + px; u < p.n_units; u += (int64_t)gridDim.x * bx) {
+        const int64_t n = u / p.tiles_per_sub;
+        int64_t t = u - n * p.tiles_per_sub;
+        int64_t a[MTTKRP_MAX_NDIM], len[MTTKRP_MAX_NDIM];
+        int64_t base = 0, vol = 1;
 #pragma unroll
-    for (int m = 0; m < MTTKRP_MAX_NDIM; ++m) {
-        a[m] = 0;
-        len[m] = 1;
-        if (m < p.ndim) {
-            if (m == p.k) {
-                base += n * p.strides[m];
-            } else {
-                const int64_t q = t / p.tiles[m];
-                const int64_t tc = t - q * p.tiles[m];
-                t = q;
-                a[m] = tc * p.width;
-                len[m] = p.dims[m] - a[m] < p.width ? p.dims[m] - a[m] : p.width;
-                base += a[m] * p.strides[m];
-                vol *= len[m];
-            }
-        }
-    }
-    for (int j = py; j < p.R; j += p.by) {
-        int64_t loc[MTTKRP_MAX_NDIM];
-#pragma unroll
-        for (int m = 0; m < MTTKRP_MAX_NDIM; ++m)
-            loc[m] = 0;
-        int64_t off = 0;
-        T pi = (T)0;
-        for (int64_t e = 0; e < vol; ++e) {
-            T phi = p.X[base + off];
-#pragma unroll
-            for (int m = 0; m < MTTKRP_MAX_NDIM; ++m)
-                if (m < p.ndim && m != p.k)
-                    phi *= p.A[m][(a[m] + loc[m]) * p.R + j];
-            pi += phi;
-            bool carry = true;
-#pragma unroll
-            for (int m = 0; m < MTTKRP_MAX_NDIM; ++m) {
-                if (m < p.ndim && m != p.k && carry) {
-                    loc[m] += 1;
-                    off += p.strides[m];
-                    if (loc[m] < len[m]) {
-                        carry = false;
-                    } else {
-                        off -= loc[m] * p.strides[m];
-                        loc[m] = 0;
-                    }
+        for (int m = 0; m < MTTKRP_MAX_NDIM; ++m) {
+            a[m] = 0;
+            len[m] = 1;
+            if (m < p.ndim) {
+                if (m == p.k) {
+                    base += n * p.strides[m];
+                } else {
+                    const int64_t q = t / p.tiles[m];
+                    const int64_t tc = t - q * p.tiles[m];
+                    t = q;
+                    a[m] = tc * p.width;
+                    len[m] = p.dims[m] - a[m] < p.width ? p.dims[m] - a[m] : p.width;
+                    base += a[m] * p.strides[m];
+                    vol *= len[m];
                 }
             }
         }
-        if (p.atomic)
-            atomic_add(&p.M[n * p.R + j], pi);
-        else
-            p.M[n * p.R + j] = pi;
+        for (int j = py; j < p.R; j += p.by) {
+            int64_t loc[MTTKRP_MAX_NDIM];
+#pragma unroll
+            for (int m = 0; m < MTTKRP_MAX_NDIM; ++m)
+                loc[m] = 0;
+            int64_t off = 0;
+            T pi = (T)0;
+            for (int64_t e = 0; e < vol; ++e) {
+                T phi = p.X[base + off];
+#pragma unroll
+                for (int m = 0; m < MTTKRP_MAX_NDIM; ++m)
+                    if (m < p.ndim && m != p.k)
+                        phi *= p.A[m][(a[m] + loc[m]) * p.R + j];
+                pi += phi;
+                bool carry = true;
+#pragma unroll
+                for (int m = 0; m < MTTKRP_MAX_NDIM; ++m) {
+                    if (m < p.ndim && m != p.k && carry) {
+                        loc[m] += 1;
+                        off += p.strides[m];
+                        if (loc[m] < len[m]) {
+                            carry = false;
+                        } else {
+                            off -= loc[m] * p.strides[m];
+                            loc[m] = 0;
+                        }
+                    }
+                }
+            }
+            if (p.atomic)
+                atomic_add(&p.M[n * p.R + j], pi);
+            else
+                p.M[n * p.R + j] = pi;
+        }
     }
 }
 
@@ -211,9 +211,9 @@ int run(int schedule, int ndim, const int64_t* dims, const T* X, const T* const*
         a.n_units = a.tiles_per_sub * dims[k];
         a.atomic = sub ? 0 : 1;
     }
-    const int64_t blocks = ceil_div(a.n_units, bx);
-    if (blocks >= ((int64_t)1 << 31))
-        return MTTKRP_ERR_UNSUPPORTED;
+    int64_t blocks = ceil_div(a.n_units, bx);
+    if (blocks > ((int64_t)1 << 24))      // 2^24 workgroups of 128 threads; the kernels stride beyond that
+        blocks = (int64_t)1 << 24;
 
     if (a.atomic) {
         const int64_t n_out = dims[k] * (int64_t)R;
