@@ -102,3 +102,22 @@ def test_ablation_errors(mt):
         mt.mttkrp_ablation(7, Xd, dims, Ad, 0, tile_width=2, M=M)
     torch.cuda.synchronize()
     assert float(M.min()) == 3.0 and float(M.max()) == 3.0     # nothing was enqueued
+
+
+def test_more_units_than_one_launch_holds(mt):
+    """More entries (ELEM) and tiles (TILE, width 1) than the 2^24 workgroups a launch
+    is given: the team threads stride over the rest.  Checked against the streaming
+    kernel, whose full-size parity has its own tests."""
+    dims, R = (512, 512, 300), 32
+    n = int(np.prod(dims))
+    X = inputs.uniform(901, n, -1.0, 1.0, dtype=torch.float32, device="cuda")
+    A = [inputs.uniform(910 + m, (I, R), -1.0, 1.0, dtype=torch.float32).cuda() for m, I in enumerate(dims)]
+    assert n // (128 // 32) > (1 << 24)
+    for k in (0, 2):
+        ref = mt.mttkrp_dense(X, dims, A, k)
+        for sched, width in ((mt.MTTKRP_SCHEDULE_ELEM, 0), (mt.MTTKRP_SCHEDULE_TILE, 1)):
+            print("ablation stride case sched=%d k=%d" % (sched, k), flush=True)
+            M = mt.mttkrp_ablation(sched, X, dims, A, k, tile_width=width)
+            torch.cuda.synchronize()
+            err = float(torch.linalg.vector_norm(M.double() - ref.double()) / torch.linalg.vector_norm(ref.double()))
+            assert err <= 2e-5, (sched, k, err)
