@@ -32,6 +32,7 @@ EXPORTED = (
     "mttkrp_timing_count", "mttkrp_timing_get", "mttkrp_timing_last",
     "mttkrp_tune_set", "mttkrp_plan_describe",
     "mttkrp_ablation_f64", "mttkrp_ablation_f32", "mttkrp_tile_volume",
+    "mttkrp_dense_all_modes_f64", "mttkrp_dense_all_modes_f32", "mttkrp_cpals_f64",
 )
 
 MTTKRP_SCHEDULE_ELEM = 1
@@ -106,6 +107,14 @@ def lib() -> ctypes.CDLL:
     L.mttkrp_tile_volume.restype = ctypes.c_int
     L.mttkrp_tile_volume.argtypes = [ctypes.c_int, i64p, ctypes.c_int64, ctypes.c_int, ctypes.c_int64,
                                      i64p, i64p]
+    for name in ("mttkrp_dense_all_modes_f64", "mttkrp_dense_all_modes_f32"):
+        getattr(L, name).restype = ctypes.c_int
+        getattr(L, name).argtypes = [ctypes.c_int, i64p, ctypes.c_void_p, vpp, ctypes.c_int, vpp,
+                                     ctypes.c_void_p]
+    L.mttkrp_cpals_f64.restype = ctypes.c_int
+    L.mttkrp_cpals_f64.argtypes = [ctypes.c_int, i64p, ctypes.c_void_p, vpp, ctypes.c_void_p, ctypes.c_int,
+                                   ctypes.c_int, ctypes.c_double, ctypes.POINTER(ctypes.c_int),
+                                   ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
     _lib = L
     return L
 
@@ -301,3 +310,49 @@ def mttkrp_tile_volume(dims: Sequence[int], cache_bytes: int, value_bytes: int,
     _check(lib().mttkrp_tile_volume(len(dims), _dims_array(dims), int(cache_bytes), int(value_bytes),
                                     int(tiles_per_unit), ctypes.byref(w), ctypes.byref(v)))
     return int(w.value), int(v.value)
+
+
+def mttkrp_dense_all_modes(X, dims: Sequence[int], factors: Sequence, M_out=None,
+                           stream: Optional[int] = None):
+    """[M_0, ..., M_{d-1}]: the MTTKRP of every mode on the same resident X."""
+    import torch
+    L = lib()
+    d = len(dims)
+    suffix, d, ptrs, R, M0, stream = _marshal(X, dims, factors, 0, None if M_out is None else M_out[0], stream)
+    if any(f is None for f in factors):
+        raise ValueError("every factor is read by the all-modes sweep")
+    if M_out is None:
+        M_out = [M0] + [torch.empty((int(dims[k]), R), dtype=X.dtype, device=X.device) for k in range(1, d)]
+    outs = (ctypes.c_void_p * d)()
+    for k in range(d):
+        M = M_out[k]
+        if (M.dtype != X.dtype or M.device != X.device or not M.is_contiguous()
+                or tuple(M.shape) != (int(dims[k]), R)):
+            raise ValueError("M_out[%d] must be a contiguous (I_k, R) tensor like X" % k)
+        outs[k] = M.data_ptr()
+    with torch.cuda.device(X.device):
+        rc = getattr(L, "mttkrp_dense_all_modes_" + suffix)(d, _dims_array(dims), X.data_ptr(), ptrs, R, outs,
+                                                            ctypes.c_void_p(stream))
+    _check(rc)
+    return list(M_out)
+
+
+def mttkrp_cpals(X, dims: Sequence[int], factors: Sequence, max_iters: int, tol: float,
+                 stream: Optional[int] = None):
+    """CP-ALS in fp64 on the GPU.  ``factors`` (initial guess) are updated in place.
+    Returns (lambda tensor, list of fits per sweep)."""
+    import torch
+    L = lib()
+    if X.dtype != torch.float64:
+        raise TypeError("CP-ALS runs in float64")
+    suffix, d, ptrs, R, _, stream = _marshal(X, dims, factors, 0, None, stream)
+    if any(f is None for f in factors):
+        raise ValueError("CP-ALS needs an initial guess for every factor")
+    lam = torch.empty(R, dtype=X.dtype, device=X.device)
+    iters = ctypes.c_int(0)
+    fits = (ctypes.c_double * int(max_iters))()
+    with torch.cuda.device(X.device):
+        rc = L.mttkrp_cpals_f64(d, _dims_array(dims), X.data_ptr(), ptrs, lam.data_ptr(), R, int(max_iters),
+                                float(tol), ctypes.byref(iters), fits, ctypes.c_void_p(stream))
+    _check(rc)
+    return lam, [float(fits[i]) for i in range(iters.value)]

@@ -1,0 +1,130 @@
+"""GPU parity of the CP-ALS driver and the all-modes sweep (include/mttkrp_cpals.h)
+against the CPU oracles, through the C ABI.
+
+The driver and the oracle start from the same seeded tensor and initial factors
+and take the same steps (see the header), so after a fixed number of sweeps the
+fits, the weights and the factors must agree to rounding.  ALS amplifies
+rounding differences slowly, so a handful of sweeps is compared at 1e-9, far
+inside what a wrong step (a transposed solve, a missing Gram update, a wrong
+norm) would produce.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_2510_14891_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mt():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2510_14891_amd import binding
+    binding.lib()
+    return binding
+
+
+def problem(dims, R, seed, rank_true=None, noise=0.0):
+    n = int(np.prod(dims))
+    if rank_true is None:
+        X = inputs.normal(seed, n, 0.0, 1.0)
+    else:
+        from oracle import cp_als_oracle
+        U = [inputs.normal(seed + 50 + m, (I, rank_true), 0.0, 1.0).numpy() for m, I in enumerate(dims)]
+        Xn = cp_als_oracle.reconstruct(U, np.ones(rank_true))
+        Xn = Xn + noise * inputs.as_ndarray_view(inputs.normal(seed, n, 0.0, 1.0), dims)
+        X = torch.from_numpy(np.ascontiguousarray(Xn.reshape(-1, order="F")))
+    A0 = [inputs.uniform(seed + 100 + m, (I, R), 0.0, 1.0) for m, I in enumerate(dims)]
+    return X, A0
+
+
+CASES = [((40, 30, 20), 5, 11), ((17, 9, 6, 5), 3, 12), ((33, 20), 4, 13), ((24, 18, 10), 16, 14),
+         ((70, 5, 9), 1, 15)]
+
+
+@pytest.mark.parametrize("dims,R,seed", CASES)
+def test_cpals_matches_the_oracle(mt, dims, R, seed):
+    from oracle import cp_als_oracle, mttkrp_oracle
+    mttkrp_oracle.build()
+    X, A0 = problem(dims, R, seed)
+    sweeps = 5
+    A_ref, lam_ref, fits_ref = cp_als_oracle.cp_als(inputs.as_ndarray_view(X, dims), [a.numpy() for a in A0], sweeps, 0.0)
+    Xd = X.cuda()
+    Ad = [a.clone().cuda() for a in A0]
+    print("cp-als case dims=%s R=%d" % (dims, R), flush=True)
+    lam, fits = mt.mttkrp_cpals(Xd, dims, Ad, sweeps, 0.0)
+    torch.cuda.synchronize()
+    assert len(fits) == sweeps == len(fits_ref)
+    np.testing.assert_allclose(fits, fits_ref, rtol=0, atol=1e-10)
+    np.testing.assert_allclose(lam.cpu().numpy(), lam_ref, rtol=1e-9)
+    for m in range(len(dims)):
+        got = Ad[m].cpu().numpy()
+        err = np.linalg.norm(got - A_ref[m]) / np.linalg.norm(A_ref[m])
+        assert err <= 1e-9, (m, err)
+
+
+def test_cpals_tolerance_stop_and_reproducibility(mt):
+    from oracle import cp_als_oracle, mttkrp_oracle
+    mttkrp_oracle.build()
+    dims, R = (30, 24, 18), 4
+    X, A0 = problem(dims, R, 21, rank_true=4, noise=0.05)
+    _, _, fits_ref = cp_als_oracle.cp_als(inputs.as_ndarray_view(X, dims), [a.numpy() for a in A0], 40, 1e-4)
+    Xd = X.cuda()
+    runs = []
+    for _ in range(2):
+        Ad = [a.clone().cuda() for a in A0]
+        lam, fits = mt.mttkrp_cpals(Xd, dims, Ad, 40, 1e-4)
+        torch.cuda.synchronize()
+        runs.append((lam.cpu().numpy().copy(), [a.cpu().numpy().copy() for a in Ad], fits))
+    assert len(runs[0][2]) == len(fits_ref)                     # same stopping sweep as the oracle
+    np.testing.assert_allclose(runs[0][2], fits_ref, rtol=0, atol=1e-8)
+    assert runs[0][2] == runs[1][2]                             # fixed-order reductions: bit-identical reruns
+    assert np.array_equal(runs[0][0], runs[1][0])
+    for a, b in zip(runs[0][1], runs[1][1]):
+        assert np.array_equal(a, b)
+
+
+def test_cpals_recovers_an_exact_low_rank_tensor(mt):
+    dims, R = (48, 40, 36), 3
+    X, A0 = problem(dims, R, 31, rank_true=3)
+    Xd = X.cuda()
+    Ad = [a.clone().cuda() for a in A0]
+    lam, fits = mt.mttkrp_cpals(Xd, dims, Ad, 300, 1e-12)
+    assert fits[-1] > 1.0 - 1e-6, fits[-5:]
+    assert all(b >= a - 1e-12 for a, b in zip(fits, fits[1:]))
+
+
+def test_all_modes_sweep(mt, oracle):
+    for dtype, tol in ((torch.float64, 1e-12), (torch.float32, 1e-5)):
+        dims, R = (70, 20, 9, 4), 24
+        n = int(np.prod(dims))
+        X = inputs.uniform(41, n, -1.0, 1.0, dtype=dtype)
+        A = [inputs.uniform(42 + m, (I, R), -1.0, 1.0, dtype=dtype) for m, I in enumerate(dims)]
+        Ms = mt.mttkrp_dense_all_modes(X.cuda(), dims, [a.cuda() for a in A])
+        torch.cuda.synchronize()
+        Xn = inputs.as_ndarray_view(X, dims)
+        for k in range(len(dims)):
+            ref = oracle.mttkrp(Xn, [a.numpy() for a in A], k)
+            assert oracle.normwise_rel_err(Ms[k].cpu().numpy(), ref) <= tol, (dtype, k)
+
+
+def test_cpals_errors(mt):
+    dims = (8, 7, 6)
+    X, A0 = problem(dims, 3, 51)
+    Xd = X.cuda()
+    with pytest.raises(mt.MttkrpError) as e:
+        big = [torch.ones((I, 65), dtype=torch.float64, device="cuda") for I in dims]
+        mt.mttkrp_cpals(Xd, dims, big, 2, 0.0)
+    assert e.value.status == mt.MTTKRP_ERR_UNSUPPORTED
+    # a zero column makes the Gram Hadamard product singular: reported, not a crash or a NaN
+    Ad = [a.clone().cuda() for a in A0]
+    Ad[1][:, 2] = 0.0
+    before = Ad[0].clone()
+    with pytest.raises(mt.MttkrpError) as e:
+        mt.mttkrp_cpals(Xd, dims, Ad, 2, 0.0)
+    assert e.value.status == mt.MTTKRP_ERR_DEVICE
+    torch.cuda.synchronize()
+    assert torch.equal(Ad[0], before)                           # the failed update left A_0 as it was
