@@ -183,6 +183,10 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     _wl("paperB_129x129x129x12x39_f64_R32", (129, 129, 129, 12, 39), "f64", 32,
         ("uniform", 0.0, 1.0), ("uniform", 0.0, 1.0), 7,
         "shape of the paper's island-coalescence tensor, random values"),
+    _wl("paperB_cp10_129x129x129x12x39_f64_R10", (129, 129, 129, 12, 39), "f64", 10,
+        ("cp_noise", 10, 0.01), ("uniform", 0.0, 1.0), 8,
+        "shape of the paper's island-coalescence tensor, rank-10 Kruskal tensor plus 1 % noise: "
+        "the CP-ALS workload (the paper runs CP-ALS on this shape at R = 10 and up)"),
 ]}
 
 
