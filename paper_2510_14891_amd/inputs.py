@@ -180,6 +180,9 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     _wl("paperA_401x201x12x501_f64_R32", (401, 201, 12, 501), "f64", 32,
         ("uniform", 0.0, 1.0), ("uniform", 0.0, 1.0), 6,
         "shape of the paper's tearing-mode tensor, random values"),
+    _wl("paperA_401x201x12x501_f64_R10", (401, 201, 12, 501), "f64", 10,
+        ("uniform", 0.0, 1.0), ("uniform", 0.0, 1.0), 6,
+        "shape of the paper's tearing-mode tensor, random values, the paper's smallest rank"),
     _wl("paperB_129x129x129x12x39_f64_R32", (129, 129, 129, 12, 39), "f64", 32,
         ("uniform", 0.0, 1.0), ("uniform", 0.0, 1.0), 7,
         "shape of the paper's island-coalescence tensor, random values"),

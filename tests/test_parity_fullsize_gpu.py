@@ -98,6 +98,8 @@ def check_workload(mt, oracle, name, rows_budget):
     ("c5_16384x2048x64_f64_R128", 8),
     ("paperA_401x201x12x501_f64_R32", 10),
     ("paperB_129x129x129x12x39_f64_R32", 10),
+    ("paperA_401x201x12x501_f64_R10", 8),
+    ("paperB_cp10_129x129x129x12x39_f64_R10", 8),
 ])
 def test_full_size_sampled_rows(mt, oracle, name, rows_budget):
     check_workload(mt, oracle, name, rows_budget)
