@@ -74,26 +74,25 @@ template <> struct Mfma<float> {
 // 17..32, the memory-bound flagship case).  The compiler places its waits for
 // outstanding loads conservatively around control flow, which keeps a wavefront
 // from overlapping its own loads with its own MFMAs; this hand-scheduled loop
-// keeps three steps of loads in flight while the MFMAs of a fourth run.  It
-// covers n = 3 + 4 * n_loop + rem consecutive unmasked steps of one sweep: X pointer
+// keeps several steps of loads in flight while the MFMAs of an earlier one run.  It
+// covers any run of at least that many consecutive unmasked steps of one sweep: X pointer
 // and factor offsets advance by constant strides, one weight Q per column block.
 // Temporaries live in fixed registers (declared as clobbers); the loads of step
-// t go to operand set t mod 4; every wait names how many later loads may still
-// be outstanding (memory operations return in issue order).
+// t go to operand set t modulo the ring size; every wait names how many later
+// loads may still be outstanding (memory operations return in issue order).
 #include "mttkrp_pipe.inc"
 
 template <bool NT>
 __device__ __forceinline__ void pipelined_run_d42(double4_t (&acc)[4][2], const double*& xq,
                                                   int64_t x_step_bytes, const double* bbase,
                                                   uint32_t bo, uint32_t b_step_bytes,
-                                                  double q0, double q1, int n_loop, int rem)
+                                                  double q0, double q1, int n_more)
 {
 #define MTTKRP_PIPE_D42_OPERANDS                                                                   \
-    [xq] "+v"(xq), [bo] "+v"(bo), [n] "+s"(n_loop), [a00] "+v"(acc[0][0]),      \
+    [xq] "+v"(xq), [bo] "+v"(bo), [n] "+s"(n_more), [a00] "+v"(acc[0][0]),      \
         [a01] "+v"(acc[0][1]), [a10] "+v"(acc[1][0]), [a11] "+v"(acc[1][1]), [a20] "+v"(acc[2][0]), \
         [a21] "+v"(acc[2][1]), [a30] "+v"(acc[3][0]), [a31] "+v"(acc[3][1])                         \
-        : [xs] "s"(x_step_bytes), [bb] "s"(bbase), [bs] "s"(b_step_bytes), [q0] "v"(q0), [q1] "v"(q1), \
-          [rem] "s"(rem)                                                                           \
+        : [xs] "s"(x_step_bytes), [bb] "s"(bbase), [bs] "s"(b_step_bytes), [q0] "v"(q0), [q1] "v"(q1) \
         : MTTKRP_PIPE_D42_CLOBBERS
     if (NT)
         asm volatile(MTTKRP_PIPE_D42_ASM_NT : MTTKRP_PIPE_D42_OPERANDS);
@@ -111,10 +110,10 @@ template <> struct HasPipe<double, 4, 2> { static constexpr bool value = true; }
 template <bool NT, typename T, int RB, int JB>
 __device__ __forceinline__ void pipelined_run(typename Mfma<T>::acc_t (&acc)[RB][JB], const T*& xq,
                                               int64_t x_step_bytes, const T* bbase, uint32_t bo,
-                                              uint32_t b_step_bytes, T q0, T q1, int n_loop, int rem)
+                                              uint32_t b_step_bytes, T q0, T q1, int n_more)
 {
     if constexpr (HasPipe<T, RB, JB>::value)
-        pipelined_run_d42<NT>(acc, xq, x_step_bytes, bbase, bo, b_step_bytes, q0, q1, n_loop, rem);
+        pipelined_run_d42<NT>(acc, xq, x_step_bytes, bbase, bo, b_step_bytes, q0, q1, n_more);
 }
 
 template <typename T> struct StreamArgs {
@@ -250,7 +249,7 @@ template <typename T, int RB, int JB> struct Budget {
 // others ("far") only change when mid wraps, and are then re-derived from the
 // linear outer index by division (rare).
 template <typename T, int RB, int JB, bool NT>
-__global__ void __launch_bounds__(kBlockThreads, (Budget<T, RB, JB>::waves))
+__global__ void __launch_bounds__(kBlockThreads, (HasPipe<T, RB, JB>::value ? MTTKRP_PIPE_D42_WAVES : Budget<T, RB, JB>::waves))
 mttkrp_stream_kernel(const StreamArgs<T> p)
 {
     // steps per batch = steps of loads in flight; where the hand-scheduled run takes the bulk
@@ -494,12 +493,10 @@ mttkrp_stream_kernel(const StreamArgs<T> p)
         if (HasPipe<T, RB, JB>::value) {
             const int avail = parked || !pipe_ok ? 0 : min(remaining, steps_plain - s_in);
             if (avail >= MTTKRP_PIPE_D42_DEPTH) {
-                const int n_loop = (avail - MTTKRP_PIPE_D42_DEPTH) / MTTKRP_PIPE_D42_RING;
                 const int n_run = avail;
-                const int rem = avail - MTTKRP_PIPE_D42_DEPTH - n_loop * MTTKRP_PIPE_D42_RING;
                 pipelined_run<NT, T, RB, JB>(acc, xp, x_step * (int64_t)sizeof(T), bbase, boff0,
                                              4u * (uint32_t)R * (uint32_t)sizeof(T),
-                                             Q[0], Q[JB > 1 ? 1 : 0], n_loop, rem);
+                                             Q[0], Q[JB > 1 ? 1 : 0], avail - MTTKRP_PIPE_D42_DEPTH);
                 bbase += (int64_t)n_run * 4 * R;
                 s_in += n_run;
                 remaining -= n_run;
