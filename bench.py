@@ -208,6 +208,21 @@ def main() -> int:
         "per_mode": per_mode,
         "roofline": roofline,
     }
+    # What the box sustains on its own (outside the timed region): a read-only pass over the same X
+    # buffer and back-to-back MFMAs of the data type for as many flops as one launch executes.
+    stream_gbps = mt.mttkrp_calibrate_stream(X, launches=10)
+    mfma_tflops = mt.mttkrp_calibrate_mfma(w.itemsize, exec_flops / 1e9, launches=10)
+    floor_ms = max(alg_bytes / (stream_gbps * 1e9), exec_flops / (mfma_tflops * 1e12)) * 1e3
+    out["ceilings_measured"] = {
+        "stream_read_GBps": round(stream_gbps, 1),
+        "mfma_TFLOPs": round(mfma_tflops, 2),
+        "floor_ms_from_probes": round(floor_ms, 4),
+        "floor_over_kernel_ms": round(floor_ms / kernel_ms, 4),
+        "how": "mttkrp_calibrate_stream over X (non-temporal 16-byte loads only) and mttkrp_calibrate_mfma "
+               "(independent 16x16x4 MFMAs on register operands, 2 N R flops per launch); floor = the larger "
+               "of bytes / stream rate and flops / MFMA rate; the MFMA probe runs 32 wavefronts per CU and "
+               "its clock drops further than the kernel's, so a ratio above 1 can occur",
+    }
     if args.cpu_budget > 0:
         out["cpu_baseline"] = cpu_baseline(w, X, A, args.cpu_budget)
     print(json.dumps(out), flush=True)

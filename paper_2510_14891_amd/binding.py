@@ -33,6 +33,7 @@ EXPORTED = (
     "mttkrp_tune_set", "mttkrp_plan_describe",
     "mttkrp_ablation_f64", "mttkrp_ablation_f32", "mttkrp_tile_volume",
     "mttkrp_dense_all_modes_f64", "mttkrp_dense_all_modes_f32", "mttkrp_cpals_f64",
+    "mttkrp_calibrate_stream", "mttkrp_calibrate_mfma",
 )
 
 MTTKRP_SCHEDULE_ELEM = 1
@@ -115,6 +116,13 @@ def lib() -> ctypes.CDLL:
     L.mttkrp_cpals_f64.argtypes = [ctypes.c_int, i64p, ctypes.c_void_p, vpp, ctypes.c_void_p, ctypes.c_int,
                                    ctypes.c_int, ctypes.c_double, ctypes.POINTER(ctypes.c_int),
                                    ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    L.mttkrp_calibrate_stream.restype = ctypes.c_int
+    L.mttkrp_calibrate_stream.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int,
+                                          ctypes.POINTER(ctypes.c_float), ctypes.c_void_p]
+    L.mttkrp_calibrate_mfma.restype = ctypes.c_int
+    L.mttkrp_calibrate_mfma.argtypes = [ctypes.c_int, ctypes.c_double, ctypes.c_int,
+                                        ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double),
+                                        ctypes.c_void_p]
     _lib = L
     return L
 
@@ -356,3 +364,29 @@ def mttkrp_cpals(X, dims: Sequence[int], factors: Sequence, max_iters: int, tol:
                                 float(tol), ctypes.byref(iters), fits, ctypes.c_void_p(stream))
     _check(rc)
     return lam, [float(fits[i]) for i in range(iters.value)]
+
+
+def mttkrp_calibrate_stream(buf, launches: int = 10, stream: Optional[int] = None) -> float:
+    """GB/s of a read-only pass over the torch tensor ``buf`` (see include/mttkrp_calibrate.h)."""
+    import torch
+    nbytes = buf.numel() * buf.element_size()
+    nbytes -= nbytes % 16
+    if stream is None:
+        stream = torch.cuda.current_stream(buf.device).cuda_stream
+    ms = ctypes.c_float(0)
+    with torch.cuda.device(buf.device):
+        _check(lib().mttkrp_calibrate_stream(buf.data_ptr(), nbytes, int(launches), ctypes.byref(ms),
+                                             ctypes.c_void_p(stream)))
+    return nbytes / ms.value / 1e6
+
+
+def mttkrp_calibrate_mfma(dtype_bytes: int, gflop_per_launch: float, launches: int = 10,
+                          stream: Optional[int] = None) -> float:
+    """TFLOP/s of back-to-back 16x16x4 MFMAs of the data type (see include/mttkrp_calibrate.h)."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    ms, flop = ctypes.c_float(0), ctypes.c_double(0)
+    _check(lib().mttkrp_calibrate_mfma(int(dtype_bytes), float(gflop_per_launch), int(launches),
+                                       ctypes.byref(ms), ctypes.byref(flop), ctypes.c_void_p(stream)))
+    return flop.value / ms.value / 1e9

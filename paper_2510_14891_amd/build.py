@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc", "mttkrp.hip")
 SRC_ABLATION = os.path.join(HERE, "csrc", "ablation.hip")
 SRC_CPALS = os.path.join(HERE, "csrc", "cpals.hip")
+SRC_CALIBRATE = os.path.join(HERE, "csrc", "calibrate.hip")
 HEADER = os.path.join(os.path.dirname(HERE), "include", "mttkrp.h")
 HEADER_ABLATION = os.path.join(os.path.dirname(HERE), "include", "mttkrp_ablation.h")
 LIB = os.path.join(HERE, "libmttkrp_hip.so")
@@ -26,14 +27,14 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if (not force and os.path.exists(LIB)
             and os.path.getmtime(LIB) >= max(os.path.getmtime(SRC), os.path.getmtime(HEADER),
                                              os.path.getmtime(SRC_ABLATION), os.path.getmtime(HEADER_ABLATION),
-                                             os.path.getmtime(SRC_CPALS),
+                                             os.path.getmtime(SRC_CPALS), os.path.getmtime(SRC_CALIBRATE),
                                              os.path.getmtime(os.path.join(HERE, "csrc", "gen_pipe.py")))):
         return LIB
     # regenerate the inline-assembly include (deterministic; the result is committed too)
     subprocess.run([sys.executable, os.path.join(HERE, "csrc", "gen_pipe.py")], check=True,
                    stdout=subprocess.DEVNULL)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB, SRC, SRC_ABLATION, SRC_CPALS]
+    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB, SRC, SRC_ABLATION, SRC_CPALS, SRC_CALIBRATE]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -315,3 +315,22 @@ def test_high_rank(mt, oracle, R):
         ws = mt.mttkrp_dense_workspace_bytes((401, 201, 12, 501), 2000, k, 8)
         krp = (401 * 201 * 12 * 501 // (401, 201, 12, 501)[k]) * 2000 * 8
         assert ws <= 128 << 20 and ws < krp / 100
+
+
+def test_calibration_probes_return_plausible_rates(mt):
+    """The two measured-ceiling probes of include/mttkrp_calibrate.h run, validate their
+    arguments and report rates of the right order for this class of GPU."""
+    buf = torch.zeros(1 << 27, dtype=torch.float64, device="cuda")      # 1 GiB
+    gbps = mt.mttkrp_calibrate_stream(buf, launches=5)
+    assert 1000.0 < gbps < 8000.0, gbps
+    for nbytes, lo, hi in ((8, 10.0, 78.6 * 1.02), (4, 20.0, 157.3 * 1.02)):
+        tf = mt.mttkrp_calibrate_mfma(nbytes, 20.0, launches=5)
+        assert lo < tf < hi, (nbytes, tf)
+    import ctypes
+    L = mt.lib()
+    ms = ctypes.c_float(0)
+    fl = ctypes.c_double(0)
+    assert L.mttkrp_calibrate_stream(buf.data_ptr() + 8, 1024, 1, ctypes.byref(ms), None) == mt.MTTKRP_ERR_INVALID_ARG
+    assert L.mttkrp_calibrate_stream(buf.data_ptr(), 1000, 1, ctypes.byref(ms), None) == mt.MTTKRP_ERR_INVALID_ARG
+    assert L.mttkrp_calibrate_mfma(2, 1.0, 1, ctypes.byref(ms), ctypes.byref(fl), None) == mt.MTTKRP_ERR_INVALID_ARG
+    assert L.mttkrp_calibrate_mfma(8, 1.0, 0, ctypes.byref(ms), ctypes.byref(fl), None) == mt.MTTKRP_ERR_INVALID_ARG
