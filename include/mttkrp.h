@@ -128,6 +128,27 @@ int mttkrp_dense_f32_ex(int ndim, const int64_t* dims, const float* X,
                         const float* lambda, float beta, float* M,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * The extended calls with leading dimensions: factors and M may be blocks of
+ * wider row-major arrays (Sec. III fixes the row-wise layout; the distance
+ * between rows is the caller's).
+ *   ld_factors  host array of d values; rows of factors[m] are ld_factors[m]
+ *               values apart, ld_factors[m] >= R (the entry for m = k is ignored)
+ *   ldM         rows of M are ldM values apart, ldM >= R; only the first R values
+ *               of every row are written (or read, with beta != 0)
+ * Everything else as for mttkrp_dense_f64_ex / _f32_ex (the same workspace size
+ * applies).  MTTKRP_ERR_INVALID_ARG also for a null ld_factors or a leading
+ * dimension below R or of 2^27 or more.
+ */
+int mttkrp_dense_f64_ld(int ndim, const int64_t* dims, const double* X,
+                        const double* const* factors, const int64_t* ld_factors, int R, int k,
+                        const double* lambda, double beta, double* M, int64_t ldM,
+                        void* workspace, size_t workspace_bytes, void* stream);
+int mttkrp_dense_f32_ld(int ndim, const int64_t* dims, const float* X,
+                        const float* const* factors, const int64_t* ld_factors, int R, int k,
+                        const float* lambda, float beta, float* M, int64_t ldM,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* Static, human-readable text for a status code. */
 const char* mttkrp_status_string(int status);
 

@@ -34,6 +34,7 @@ EXPORTED = (
     "mttkrp_ablation_f64", "mttkrp_ablation_f32", "mttkrp_tile_volume",
     "mttkrp_dense_all_modes_f64", "mttkrp_dense_all_modes_f32", "mttkrp_cpals_f64",
     "mttkrp_calibrate_stream", "mttkrp_calibrate_mfma",
+    "mttkrp_dense_f64_ld", "mttkrp_dense_f32_ld",
 )
 
 MTTKRP_SCHEDULE_ELEM = 1
@@ -116,6 +117,13 @@ def lib() -> ctypes.CDLL:
     L.mttkrp_cpals_f64.argtypes = [ctypes.c_int, i64p, ctypes.c_void_p, vpp, ctypes.c_void_p, ctypes.c_int,
                                    ctypes.c_int, ctypes.c_double, ctypes.POINTER(ctypes.c_int),
                                    ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    ldargs = [ctypes.c_int, i64p, ctypes.c_void_p, vpp, i64p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    L.mttkrp_dense_f64_ld.restype = ctypes.c_int
+    L.mttkrp_dense_f64_ld.argtypes = ldargs + [ctypes.c_double, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                               ctypes.c_size_t, ctypes.c_void_p]
+    L.mttkrp_dense_f32_ld.restype = ctypes.c_int
+    L.mttkrp_dense_f32_ld.argtypes = ldargs + [ctypes.c_float, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                               ctypes.c_size_t, ctypes.c_void_p]
     L.mttkrp_calibrate_stream.restype = ctypes.c_int
     L.mttkrp_calibrate_stream.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int,
                                           ctypes.POINTER(ctypes.c_float), ctypes.c_void_p]
@@ -390,3 +398,43 @@ def mttkrp_calibrate_mfma(dtype_bytes: int, gflop_per_launch: float, launches: i
     _check(lib().mttkrp_calibrate_mfma(int(dtype_bytes), float(gflop_per_launch), int(launches),
                                        ctypes.byref(ms), ctypes.byref(flop), ctypes.c_void_p(stream)))
     return flop.value / ms.value / 1e9
+
+
+def mttkrp_dense_ld(X, dims: Sequence[int], factors: Sequence, k: int, M, R: int, lam=None,
+                    beta: float = 0.0, stream: Optional[int] = None):
+    """The MTTKRP on blocks of wider arrays: ``factors[m]`` are 2-D torch tensors
+    (I_m, >= R) whose rows may be strided (stride(1) == 1), of which the first R
+    columns are the factor; ``M`` likewise (I_k, >= R), of which the first R
+    columns are written.  See mttkrp_dense_f64_ld in include/mttkrp.h."""
+    import torch
+    L = lib()
+    d = len(dims)
+    suffix = "f64" if X.dtype == torch.float64 else "f32"
+    if X.dtype not in (torch.float64, torch.float32) or not X.is_cuda or not X.is_contiguous():
+        raise ValueError("X must be a contiguous float64/float32 tensor on the GPU")
+    ptrs = (ctypes.c_void_p * d)()
+    lds = (ctypes.c_int64 * d)()
+    for m in range(d):
+        A = factors[m]
+        if A is None:
+            ptrs[m] = None
+            lds[m] = R
+            continue
+        if (A.dtype != X.dtype or A.device != X.device or A.dim() != 2 or A.shape[0] != int(dims[m])
+                or A.shape[1] < R or (A.shape[1] > 1 and A.stride(1) != 1)):
+            raise ValueError("factor %d: wrong dtype/device/shape/strides" % m)
+        ptrs[m] = A.data_ptr()
+        lds[m] = A.stride(0) if A.shape[0] > 1 else max(R, A.shape[1])
+    if (M.dtype != X.dtype or M.device != X.device or M.dim() != 2 or M.shape[0] != int(dims[k])
+            or M.shape[1] < R or (M.shape[1] > 1 and M.stride(1) != 1)):
+        raise ValueError("M: wrong dtype/device/shape/strides")
+    ldM = M.stride(0) if M.shape[0] > 1 else max(R, M.shape[1])
+    if stream is None:
+        stream = torch.cuda.current_stream(X.device).cuda_stream
+    with torch.cuda.device(X.device):
+        rc = getattr(L, "mttkrp_dense_" + suffix + "_ld")(
+            d, _dims_array(dims), X.data_ptr(), ptrs, lds, int(R), int(k),
+            lam.data_ptr() if lam is not None else None, float(beta), M.data_ptr(), int(ldM),
+            None, 0, ctypes.c_void_p(stream))
+    _check(rc)
+    return M

@@ -335,3 +335,47 @@ def test_calibration_probes_return_plausible_rates(mt):
     assert L.mttkrp_calibrate_stream(buf.data_ptr(), 1000, 1, ctypes.byref(ms), None) == mt.MTTKRP_ERR_INVALID_ARG
     assert L.mttkrp_calibrate_mfma(2, 1.0, 1, ctypes.byref(ms), ctypes.byref(fl), None) == mt.MTTKRP_ERR_INVALID_ARG
     assert L.mttkrp_calibrate_mfma(8, 1.0, 0, ctypes.byref(ms), ctypes.byref(fl), None) == mt.MTTKRP_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+def test_leading_dimensions(mt, oracle, dtype):
+    """Factors and M as column blocks of wider row-major arrays (the *_ld calls): the
+    padding is NaN in the factors and must never be read, and the padding of M must
+    stay untouched.  Shapes cover direct writes (one slot) and the combine kernel."""
+    for dims, R, pads in (((70, 9, 6, 5), 24, (3, 0, 8, 1)), ((200, 36, 14), 7, (1, 5, 2)), ((33, 20), 33, (2, 7)),
+                          ((16, 4, 3), 16, (4, 4, 4))):
+        X, A = make_problem(dims, R, dtype, seed=61 + len(dims))
+        Xd = X.cuda()
+        wide = []
+        for m, a in enumerate(A):
+            buf = torch.full((dims[m], R + pads[m]), float("nan"), dtype=dtype, device="cuda")
+            buf[:, :R] = a.cuda()
+            wide.append(buf)
+        lam = inputs.uniform(99, R, 0.5, 1.5, dtype=dtype)
+        Xn = inputs.as_ndarray_view(X, dims)
+        An = [a.numpy() for a in A]
+        for k in range(len(dims)):
+            print("ld case dims=%s R=%d %s k=%d" % (dims, R, dtype, k), flush=True)
+            ref = oracle.mttkrp(Xn, An, k, lam=lam.numpy())
+            Mw = torch.full((dims[k], R + 5), 7.0, dtype=dtype, device="cuda")
+            mt.mttkrp_dense_ld(Xd, dims, [w[:, :R] for w in wide], k, Mw[:, :R], R, lam=lam.cuda())
+            torch.cuda.synchronize()
+            got = Mw[:, :R].cpu().numpy()
+            assert oracle.normwise_rel_err(got, ref) <= TOL[dtype], (dims, R, k)
+            assert bool((Mw[:, R:] == 7.0).all())
+            # accumulation through the padded M
+            Mw[:, :R] = 1.0
+            mt.mttkrp_dense_ld(Xd, dims, [w[:, :R] for w in wide], k, Mw[:, :R], R, beta=2.0)
+            torch.cuda.synchronize()
+            ref2 = oracle.mttkrp(Xn, An, k) + 2.0
+            assert oracle.normwise_rel_err(Mw[:, :R].cpu().numpy(), ref2) <= TOL[dtype], (dims, R, k)
+            assert bool((Mw[:, R:] == 7.0).all())
+    L = mt.lib()
+    import ctypes
+    d3 = (ctypes.c_int64 * 3)(4, 4, 4)
+    bad = (ctypes.c_int64 * 3)(3, 4, 4)
+    one = ctypes.c_void_p(16)
+    ptrs = (ctypes.c_void_p * 3)(16, 16, 16)
+    assert L.mttkrp_dense_f64_ld(3, d3, one, ptrs, bad, 4, 1, None, 0.0, one, 4, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
+    assert L.mttkrp_dense_f64_ld(3, d3, one, ptrs, d3, 4, 1, None, 0.0, one, 3, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
+    assert L.mttkrp_dense_f64_ld(3, d3, one, ptrs, None, 4, 1, None, 0.0, one, 4, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
