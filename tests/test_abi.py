@@ -81,7 +81,10 @@ def test_workspace_stays_in_the_sum_of_dims_class(mt):
             assert ws <= 0.04 * x_bytes + (64 << 20), (name, k, ws)
             desc = mt.mttkrp_plan_describe(w.dims, w.R, k, w.itemsize)
             slots = int(re.search(r"slots=(\d+)", desc).group(1))
-            assert ws == (slots * w.dims[k] * w.R * w.itemsize if slots > 1 else 0)
+            fused = int(re.search(r"fused_bytes=(\d+)", desc).group(1))
+            part = slots * w.dims[k] * w.R * w.itemsize if slots > 1 else 0
+            assert ws == (part + 255) // 256 * 256 + fused
+            assert fused <= (8 << 20)        # the product matrix of two fused modes stays small
             assert slots <= 4096, (name, k, slots)
 
 
