@@ -380,3 +380,36 @@ def test_leading_dimensions(mt, oracle, dtype):
     assert L.mttkrp_dense_f64_ld(3, d3, one, ptrs, bad, 4, 1, None, 0.0, one, 4, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
     assert L.mttkrp_dense_f64_ld(3, d3, one, ptrs, d3, 4, 1, None, 0.0, one, 3, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
     assert L.mttkrp_dense_f64_ld(3, d3, one, ptrs, None, 4, 1, None, 0.0, one, 4, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
+
+
+def test_seeded_random_shapes(mt, oracle):
+    """Eighty seeded random problems (2 to 6 modes, extents 1 to 70, R 1 to 80, both data
+    types, every mode): a sweep over the planner's decisions (tile shapes, fused modes,
+    kernel builds, splits) that no hand-picked list covers."""
+    u = inputs.uniform(20240601, 80 * 16).numpy()
+    t = 0
+    for case in range(80):
+        d = 2 + int(u[t] * 5); t += 1
+        big = int(u[t] * d); t += 1                       # one mode may be larger
+        dims = []
+        for m in range(d):
+            hi = 70 if m == big else (24 if d <= 4 else 9)
+            dims.append(1 + int(u[t] * hi)); t += 1
+        R = 1 + int(u[t] * 80); t += 1
+        dtype = torch.float64 if u[t] < 0.6 else torch.float32; t += 1
+        t = (t + 15) // 16 * 16
+        if int(np.prod(dims)) > 3_000_000:
+            continue
+        X, A = make_problem(tuple(dims), R, dtype, seed=7000 + case)
+        Xd = X.cuda()
+        Ad = [a.cuda() for a in A]
+        Xn = inputs.as_ndarray_view(X, dims)
+        An = [a.numpy() for a in A]
+        for k in range(d):
+            print("random case %d dims=%s R=%d %s k=%d %s" % (case, dims, R, dtype, k, mt.mttkrp_plan_describe(
+                dims, R, k, 8 if dtype == torch.float64 else 4)), flush=True)
+            M = mt.mttkrp_dense(Xd, dims, Ad, k)
+            torch.cuda.synchronize()
+            ref = oracle.mttkrp(Xn, An, k)
+            err = oracle.normwise_rel_err(M.cpu().numpy(), ref)
+            assert err <= TOL[dtype], (case, dims, R, k, err)
