@@ -11,7 +11,9 @@
  * which equals X_(k) * (A_d (.) ... (.) A_{k+1} (.) A_{k-1} (.) ... (.) A_1) of
  * Eq. (krp) without ever forming the Khatri-Rao matrix or an unfolded or
  * permuted copy of X.  Extra device memory is O(R * sum_n I_n)-class partial
- * sums only (Sec. I, contributions; Sec. II-B last paragraph).
+ * sums (Sec. I, contributions; Sec. II-B last paragraph) plus, where two short
+ * adjacent modes are treated as one, the row-wise product of their two factors,
+ * which is only formed while it stays below a constant size (8 MiB by default).
  *
  * Layouts (Sec. II-A: ind2sub/sub2ind "defined like MATLAB" => first index
  * fastest; Sec. III: row-wise factor layout):
