@@ -199,6 +199,8 @@ int mttkrp_timing_last(float* stream_ms, float* combine_ms);
  *   "nt_loads"      1 = never use non-temporal tensor loads, 0 = chosen by alignment
  *   "fuse_bytes"    largest product matrix (bytes) for which two adjacent short modes
  *                   are fused into one (default 8 MiB; 1 = never fuse)
+ *   "inner_splits"  pieces the sweep over the inner column mode is cut into (1..64),
+ *                   0 = chosen by the planner
  *   "deep"          1 = always the kernel build with the software-pipelined run,
  *                   2 = always the build with batches only, 0 = by item length
  * Returns MTTKRP_ERR_INVALID_ARG for an unknown key or a value out of range.

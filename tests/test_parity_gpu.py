@@ -31,7 +31,7 @@ def mt():
 
 
 TUNE_KEYS = ("row_blocks", "target_items", "max_steps", "xcd_remap", "ws_percent",
-             "max_col_blocks", "first_group", "deep", "waves_per_simd", "nt_loads", "fuse_bytes")
+             "max_col_blocks", "first_group", "deep", "waves_per_simd", "nt_loads", "fuse_bytes", "inner_splits")
 
 
 def make_problem(dims, R, dtype, seed, dist=("uniform", -1.0, 1.0)):
@@ -236,7 +236,7 @@ def test_result_does_not_depend_on_the_decomposition(mt, oracle, dtype):
         {"max_col_blocks": 1}, {"first_group": 1}, {"first_group": 4},
         {"first_group": 1, "ws_percent": 100, "target_items": 50000},
         {"deep": 1}, {"deep": 2}, {"deep": 1, "max_steps": 8}, {"nt_loads": 1}, {"waves_per_simd": 2},
-        {"fuse_bytes": 1}, {"fuse_bytes": 1 << 30}, {"fuse_bytes": 1 << 30, "target_items": 64},
+        {"fuse_bytes": 1}, {"inner_splits": 1}, {"inner_splits": 5}, {"fuse_bytes": 1 << 30}, {"fuse_bytes": 1 << 30, "target_items": 64},
     ]
     try:
         for st in settings:
