@@ -11,9 +11,11 @@
  * which equals X_(k) * (A_d (.) ... (.) A_{k+1} (.) A_{k-1} (.) ... (.) A_1) of
  * Eq. (krp) without ever forming the Khatri-Rao matrix or an unfolded or
  * permuted copy of X.  Extra device memory is O(R * sum_n I_n)-class partial
- * sums (Sec. I, contributions; Sec. II-B last paragraph) plus, where two short
- * adjacent modes are treated as one, the row-wise product of their two factors,
- * which is only formed while it stays below a constant size (8 MiB by default).
+ * sums (Sec. I, contributions; Sec. II-B last paragraph) plus, where two
+ * adjacent modes are treated as one (two short column modes; modes 0 and 1 when
+ * I_0 fits the 16-row MFMA blocks badly), the row-wise product of their two
+ * factors, which is only formed while it stays below a constant size (8 MiB by
+ * default; at most two such matrices per call).
  *
  * Layouts (Sec. II-A: ind2sub/sub2ind "defined like MATLAB" => first index
  * fastest; Sec. III: row-wise factor layout):
@@ -197,7 +199,7 @@ int mttkrp_timing_last(float* stream_ms, float* combine_ms);
  *   "waves_per_simd"  cap on resident wavefronts per SIMD (2..7; enforced by
  *                   reserving LDS), 0 = whatever the registers allow
  *   "nt_loads"      1 = never use non-temporal tensor loads, 0 = chosen by alignment
- *   "fuse_bytes"    largest product matrix (bytes) for which two adjacent short modes
+ *   "fuse_bytes"    largest product matrix (bytes) for which two adjacent modes
  *                   are fused into one (default 8 MiB; 1 = never fuse)
  *   "inner_splits"  pieces the sweep over the inner column mode is cut into (1..64),
  *                   0 = chosen by the planner

@@ -382,6 +382,38 @@ def test_leading_dimensions(mt, oracle, dtype):
     assert L.mttkrp_dense_f64_ld(3, d3, one, ptrs, None, 4, 1, None, 0.0, one, 4, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
 
 
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+def test_fused_row_modes(mt, oracle, dtype):
+    """Modes 0 and 1 treated as one row mode (their factors' row-wise product stands in for
+    A_0): shapes for which the planner reports it, alone and together with a fused column pair,
+    through the plain call and through the call with leading dimensions (NaN padding)."""
+    cases = (((19, 5, 9, 300), 20, 2), ((19, 5, 40, 3, 50), 7, 2), ((45, 45, 24, 7, 6), 32, 2), ((33, 6, 4, 3, 5), 33, 2))
+    for dims, R, k in cases:
+        desc = mt.mttkrp_plan_describe(dims, R, k, 8 if dtype == torch.float64 else 4)
+        print("fused rows dims=%s R=%d %s k=%d %s" % (dims, R, dtype, k, desc), flush=True)
+        assert "fused_rows=1" in desc, desc
+        X, A = make_problem(dims, R, dtype, seed=83 + len(dims))
+        ref = oracle_mttkrp(oracle, X, dims, A, k)
+        got = gpu_mttkrp(mt, X, dims, A, k)
+        assert oracle.normwise_rel_err(got, ref) <= TOL[dtype], (dims, R, k)
+        wide = []
+        for m, a in enumerate(A):
+            buf = torch.full((dims[m], R + 3 + m), float("nan"), dtype=dtype, device="cuda")
+            buf[:, :R] = a.cuda()
+            wide.append(buf)
+        Mw = torch.full((dims[k], R + 2), 7.0, dtype=dtype, device="cuda")
+        mt.mttkrp_dense_ld(X.cuda(), dims, [w[:, :R] for w in wide], k, Mw[:, :R], R)
+        torch.cuda.synchronize()
+        assert oracle.normwise_rel_err(Mw[:, :R].cpu().numpy(), ref) <= TOL[dtype], (dims, R, k)
+        assert bool((Mw[:, R:] == 7.0).all())
+    # never with the fusing switched off
+    mt.mttkrp_tune_set("fuse_bytes", 1)
+    try:
+        assert "fused_rows=0" in mt.mttkrp_plan_describe((19, 5, 9, 300), 20, 2, 8)
+    finally:
+        mt.mttkrp_tune_set("fuse_bytes", 0)
+
+
 def test_seeded_random_shapes(mt, oracle):
     """Eighty seeded random problems (2 to 6 modes, extents 1 to 70, R 1 to 80, both data
     types, every mode): a sweep over the planner's decisions (tile shapes, fused modes,
