@@ -31,7 +31,7 @@ def mt():
 
 
 TUNE_KEYS = ("row_blocks", "target_items", "max_steps", "xcd_remap", "ws_percent",
-             "max_col_blocks", "first_group", "deep", "waves_per_simd", "nt_loads", "fuse_bytes", "inner_splits")
+             "max_col_blocks", "first_group", "deep", "waves_per_simd", "nt_loads", "fuse_bytes", "inner_splits", "contract_rows", "rows_col_blocks")
 
 
 def make_problem(dims, R, dtype, seed, dist=("uniform", -1.0, 1.0)):
@@ -236,6 +236,8 @@ def test_result_does_not_depend_on_the_decomposition(mt, oracle, dtype):
         {"max_col_blocks": 1}, {"first_group": 1}, {"first_group": 4},
         {"first_group": 1, "ws_percent": 100, "target_items": 50000},
         {"deep": 1}, {"deep": 2}, {"deep": 1, "max_steps": 8}, {"nt_loads": 1}, {"waves_per_simd": 2},
+        {"contract_rows": 1}, {"contract_rows": 1, "max_steps": 3}, {"contract_rows": 1, "max_col_blocks": 1},
+        {"contract_rows": 2},
         {"fuse_bytes": 1}, {"inner_splits": 1}, {"inner_splits": 5}, {"fuse_bytes": 1 << 30}, {"fuse_bytes": 1 << 30, "target_items": 64},
     ]
     try:
@@ -380,6 +382,63 @@ def test_leading_dimensions(mt, oracle, dtype):
     assert L.mttkrp_dense_f64_ld(3, d3, one, ptrs, bad, 4, 1, None, 0.0, one, 4, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
     assert L.mttkrp_dense_f64_ld(3, d3, one, ptrs, d3, 4, 1, None, 0.0, one, 3, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
     assert L.mttkrp_dense_f64_ld(3, d3, one, ptrs, None, 4, 1, None, 0.0, one, 4, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+def test_row_contraction_schedule(mt, oracle, dtype):
+    """The second schedule (MFMA contraction over mode 0, weights of the column space applied
+    in the epilogue) computes the same sum of Eq. (elem): forced on for shapes with one and
+    with two column pieces (modes below and above k), ragged row counts, column counts and R
+    beyond one tile, many row splits; plain call, leading dimensions, lambda and beta."""
+    sb = 8 if dtype == torch.float64 else 4
+    shapes = [((300, 7, 9), 16), ((1000, 5, 4, 3), 5), ((130, 3, 2, 2), 33), ((64, 64, 64), 16), ((17, 40, 6), 70),
+              ((5, 300), 7), ((2048, 9, 11), 100), ((520, 3, 50), 24), ((777, 2, 3, 2, 5), 40)]
+    try:
+        for tune in ({"contract_rows": 1}, {"contract_rows": 1, "max_steps": 2}, {"contract_rows": 1, "rows_col_blocks": 1}):
+            for key, val in tune.items():
+                mt.mttkrp_tune_set(key, val)
+            for dims, R in shapes:
+                X, A = make_problem(dims, R, dtype, seed=71 + len(dims))
+                Xn = inputs.as_ndarray_view(X, dims)
+                An = [a.numpy() for a in A]
+                Xd = X.cuda()
+                Ad = [a.cuda() for a in A]
+                lam = inputs.uniform(98, R, 0.5, 1.5, dtype=dtype)
+                for k in range(1, len(dims)):
+                    desc = mt.mttkrp_plan_describe(dims, R, k, sb)
+                    print("rows schedule %s dims=%s R=%d %s k=%d %s" % (tune, dims, R, dtype, k, desc), flush=True)
+                    assert "shape=rows" in desc, desc
+                    ref = oracle.mttkrp(Xn, An, k)
+                    got = mt.mttkrp_dense(Xd, dims, Ad, k)
+                    torch.cuda.synchronize()
+                    assert oracle.normwise_rel_err(got.cpu().numpy(), ref) <= TOL[dtype], (dims, R, k)
+                    # leading dimensions, lambda, accumulation
+                    wide = []
+                    for m, a in enumerate(A):
+                        buf = torch.full((dims[m], R + 1 + m), float("nan"), dtype=dtype, device="cuda")
+                        buf[:, :R] = Ad[m]
+                        wide.append(buf)
+                    Mw = torch.full((dims[k], R + 3), 1.0, dtype=dtype, device="cuda")
+                    mt.mttkrp_dense_ld(Xd, dims, [w[:, :R] for w in wide], k, Mw[:, :R], R, lam=lam.cuda(), beta=0.5)
+                    torch.cuda.synchronize()
+                    ref2 = oracle.mttkrp(Xn, An, k, lam=lam.numpy()) + 0.5
+                    assert oracle.normwise_rel_err(Mw[:, :R].cpu().numpy(), ref2) <= TOL[dtype], (dims, R, k)
+                    assert bool((Mw[:, R:] == 1.0).all())
+            for key in tune:
+                mt.mttkrp_tune_set(key, 0)
+        # chosen by the planner itself: few column entries, long mode 0 (2053 rows: a ragged last step)
+        dims, R = (2053, 16, 12), 50
+        X, A = make_problem(dims, R, dtype, seed=77)
+        for k in (1, 2):
+            desc = mt.mttkrp_plan_describe(dims, R, k, sb)
+            assert ("shape=rows" in desc) == (dtype == torch.float64), desc
+            got = gpu_mttkrp(mt, X, dims, A, k)
+            assert oracle.normwise_rel_err(got, oracle_mttkrp(oracle, X, dims, A, k)) <= TOL[dtype], (dims, k)
+        mt.mttkrp_tune_set("contract_rows", 2)
+        assert "shape=rows" not in mt.mttkrp_plan_describe(dims, R, 1, sb)
+    finally:
+        for key in TUNE_KEYS:
+            mt.mttkrp_tune_set(key, 0)
 
 
 @pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
