@@ -88,6 +88,25 @@ def test_workspace_stays_in_the_sum_of_dims_class(mt):
             assert slots <= 4096, (name, k, slots)
 
 
+def test_workspace_bounded_for_short_column_spaces(mt):
+    """Sec. I / II-B memory claim on shapes where the modes other than 0 and k have few entries
+    and the rank is high: one partial row of M per row block would approach the size of X, so
+    the planner must switch to the schedule whose partial sums stay small."""
+    cases = [((20000, 20000, 7), 500, 1, 4), ((4096, 4096, 32), 2000, 1, 8), ((1000, 2, 1, 20000), 100, 3, 4),
+             ((33, 20000, 1), 500, 1, 8), ((401, 20000), 500, 1, 4), ((16384, 2048, 64), 128, 1, 8)]
+    for dims, R, k, sb in cases:
+        n = 1
+        for d in dims:
+            n *= d
+        ws = mt.mttkrp_dense_workspace_bytes(dims, R, k, sb)
+        assert ws <= 0.05 * n * sb + (64 << 20), (dims, R, k, ws)
+        desc = mt.mttkrp_plan_describe(dims, R, k, sb)
+        slots = int(re.search(r"slots=(\d+)", desc).group(1))
+        fused = int(re.search(r"fused_bytes=(\d+)", desc).group(1))
+        part = slots * dims[k] * R * sb if slots > 1 else 0
+        assert ws == (part + 255) // 256 * 256 + fused, desc
+
+
 def test_tile_volume_matches_the_oracle(mt):
     """Eq. (heuristic): the library's integer arithmetic against the oracle's exact
     rational arithmetic, value for value (host only)."""
