@@ -505,3 +505,47 @@ def test_seeded_random_shapes(mt, oracle):
             ref = oracle.mttkrp(Xn, An, k)
             err = oracle.normwise_rel_err(M.cpu().numpy(), ref)
             assert err <= TOL[dtype], (case, dims, R, k, err)
+
+
+def test_seeded_random_shapes_long_first_mode(mt, oracle):
+    """A hundred and fifty seeded random problems with a long or ragged mode 0 and short other
+    modes, under seeded planner settings: the shapes that reach the fused row mode, the second
+    schedule (one and two column pieces, many row splits, ragged last steps) and their
+    combinations with the tuning keys."""
+    I0s = (1, 5, 16, 17, 63, 129, 257, 300, 520, 1000, 2053, 4100)
+    Is = (1, 2, 3, 4, 5, 7, 9, 12, 16, 17, 33, 40, 64)
+    Rs = (1, 3, 8, 16, 17, 32, 33, 49, 50, 64, 70, 100)
+    tunes = ({}, {}, {"contract_rows": 1}, {"contract_rows": 1, "max_steps": 2}, {"contract_rows": 2},
+             {"contract_rows": 1, "target_items": 100000}, {"fuse_bytes": 1 << 30}, {"target_items": 50000},
+             {"contract_rows": 1, "rows_col_blocks": 1}, {"inner_splits": 3}, {"max_steps": 3})
+    u = inputs.uniform(20240607, 150 * 16).numpy()
+    try:
+        for case in range(150):
+            t = case * 16
+            d = (2, 3, 3, 3, 4, 4, 5, 6)[int(u[t] * 8)]
+            dims = [I0s[int(u[t + 1] * len(I0s))]] + [Is[int(u[t + 2 + m] * len(Is))] for m in range(d - 1)]
+            while int(np.prod(dims)) > 400_000:
+                i = int(np.argmax(dims))
+                dims[i] = max(1, dims[i] // 2)
+            R = Rs[int(u[t + 8] * len(Rs))]
+            dtype = torch.float64 if u[t + 9] < 0.6 else torch.float32
+            tune = tunes[int(u[t + 10] * len(tunes))]
+            X, A = make_problem(tuple(dims), R, dtype, seed=8000 + case)
+            Xd = X.cuda()
+            Ad = [a.cuda() for a in A]
+            Xn = inputs.as_ndarray_view(X, dims)
+            An = [a.numpy() for a in A]
+            for key, val in tune.items():
+                mt.mttkrp_tune_set(key, val)
+            for k in range(d):
+                print("random long case %d dims=%s R=%d %s k=%d tune=%s %s" % (case, dims, R, dtype, k, tune,
+                      mt.mttkrp_plan_describe(dims, R, k, 8 if dtype == torch.float64 else 4)), flush=True)
+                M = mt.mttkrp_dense(Xd, dims, Ad, k)
+                torch.cuda.synchronize()
+                err = oracle.normwise_rel_err(M.cpu().numpy(), oracle.mttkrp(Xn, An, k))
+                assert err <= TOL[dtype], (case, dims, R, k, tune, err)
+            for key in tune:
+                mt.mttkrp_tune_set(key, 0)
+    finally:
+        for key in TUNE_KEYS:
+            mt.mttkrp_tune_set(key, 0)
