@@ -28,11 +28,12 @@ def build(force: bool = True, verbose: bool = False) -> str:
             and os.path.getmtime(LIB) >= max(os.path.getmtime(SRC), os.path.getmtime(HEADER),
                                              os.path.getmtime(SRC_ABLATION), os.path.getmtime(HEADER_ABLATION),
                                              os.path.getmtime(SRC_CPALS), os.path.getmtime(SRC_CALIBRATE),
-                                             os.path.getmtime(os.path.join(HERE, "csrc", "gen_pipe.py")))):
+                                             os.path.getmtime(os.path.join(HERE, "csrc", "gen_pipe.py")),
+                                             os.path.getmtime(os.path.join(HERE, "csrc", "gen_rows_pipe.py")))):
         return LIB
     # regenerate the inline-assembly include (deterministic; the result is committed too)
-    subprocess.run([sys.executable, os.path.join(HERE, "csrc", "gen_pipe.py")], check=True,
-                   stdout=subprocess.DEVNULL)
+    for gen in ("gen_pipe.py", "gen_rows_pipe.py"):
+        subprocess.run([sys.executable, os.path.join(HERE, "csrc", gen)], check=True, stdout=subprocess.DEVNULL)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB, SRC, SRC_ABLATION, SRC_CPALS, SRC_CALIBRATE]
     if verbose:

@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Writes mttkrp_rows_pipe.inc: the software-pipelined inner loops of the second
+schedule (mttkrp_rowsum_kernel, contraction over mode 0) as inline assembly, one
+per instantiation (data type, column blocks CB of the column space, output column
+blocks JB).
+
+Why assembly: as compiled from plain HIP, the ring of operand sets of that kernel
+waits for all outstanding loads at the top of every pass (the compiler's waits
+are conservative across the loop's back edge), so a wavefront never overlaps its
+own loads with its own MFMAs.  The generated loop keeps D steps of loads in flight
+while the MFMAs of an earlier step run, as gen_pipe.py does for the streaming
+kernel; the structure (ring of D + 1 operand sets at the top of the register
+budget, exit check per step, one drain tail per ring position, waits that name how
+many younger loads may be outstanding) is the same.
+
+One step = 16 rows of mode 0: for each of the CB column blocks the lane's four
+tensor rows (fp32: one 16-byte load; fp64: two, 64 bytes apart, so that the four
+lanes of a column read one whole 64-byte sector per load), for each of the four rows t
+the lane's JB entries of that row of A_0 (one or two loads in the wide column
+layout `Lay` of mttkrp.hip), and 4 * CB * JB 16x16x4 MFMAs: MFMA (t, cb, jb) takes
+row t of column block cb and of output column block jb.  The tensor pointers (one
+per column block, per lane) advance by 16 rows, the byte offsets into A_0 (per
+lane, relative to four wave-uniform row pointers) by 16 rows of A_0.
+
+Run by build.py before hipcc; the output is committed so that the library also
+builds without running this script.
+"""
+import os
+
+D_MAX = int(os.environ.get("MTTKRP_GEN_ROWS_DEPTH", "3"))
+OTHERS = {2: 46, 1: 44}      # registers the rest of the kernel keeps live across a run (fp64, fp32)
+X_FLAGS = os.environ.get("MTTKRP_GEN_ROWS_XFLAGS", "")   # cache policy of the tensor loads (experiments), e.g. " nt"
+TILES = [(1, 1), (1, 2), (1, 3), (1, 4), (2, 1), (2, 2), (2, 3), (2, 4), (3, 1), (3, 2), (4, 1), (4, 2)]
+
+
+class Inst:
+    def __init__(self, w, cb, jb):
+        self.w, self.cb, self.jb = w, cb, jb            # w: registers per value (2 = fp64, 1 = fp32)
+        self.xregs = cb * 4 * w
+        self.brow = jb * w + ((jb * w) & 1)             # registers per row of A_0 entries (register tuples start even)
+        self.bregs = 4 * self.brow
+        self.set = self.xregs + self.bregs
+        self.acc = cb * jb * 4 * w
+        g = 16 // (4 * w)                               # values per 16-byte load
+        self.n0 = min(jb, g)
+        self.n1 = jb - self.n0
+        self.xloads = w                                 # load instructions per column block
+        self.loads = cb * self.xloads + 4 * (1 + (1 if self.n1 else 0))
+        self.pick()
+
+    def ring(self, d):
+        return self.set * (d + 1)
+
+    def pick(self):
+        # the most wavefronts per SIMD for which at least two steps in flight fit, else one step at two wavefronts
+        self.budget = 0
+        for d_min in (2, 1):
+            for budget, waves in ((128, 4), (168, 3), (256, 2)):
+                for d in range(D_MAX, d_min - 1, -1):
+                    if d * self.loads > 63:
+                        continue
+                    if self.acc + OTHERS[self.w] + self.ring(d) <= budget:
+                        self.budget, self.waves, self.d = budget, waves, d
+                        self.t0 = budget - self.ring(d)
+                        self.t0 -= self.t0 & 1
+                        return
+
+    def tag(self):
+        return "%s%d%d" % ("d" if self.w == 2 else "f", self.cb, self.jb)
+
+    def ctype(self):
+        return "double" if self.w == 2 else "float"
+
+    # --- registers
+    @staticmethod
+    def reg(base, n):
+        return "v%d" % base if n == 1 else "v[%d:%d]" % (base, base + n - 1)
+
+    def base(self, s):
+        return self.t0 + self.set * s
+
+    def xval(self, s, c, t):
+        return self.reg(self.base(s) + (c * 4 + t) * self.w, self.w)
+
+    def bval(self, s, t, j):
+        return self.reg(self.base(s) + self.xregs + t * self.brow + j * self.w, self.w)
+
+    def last_reg(self):
+        return self.t0 + self.ring(self.d) - 1
+
+    # --- code
+    def issue(self, s):
+        o = []
+        width = {1: "dword", 2: "dwordx2", 3: "dwordx3", 4: "dwordx4"}
+        for c in range(self.cb):
+            for h in range(self.xloads):
+                o.append("global_load_dwordx4 %s, %%[x%d], off%s" % (
+                    self.reg(self.base(s) + c * 4 * self.w + 4 * h, 4), c, (" offset:64" if h else "") + X_FLAGS))
+        for t in range(4):
+            o.append("global_load_%s %s, %%[bo0], %%[bb%d]" % (
+                width[self.n0 * self.w], self.reg(self.base(s) + self.xregs + t * self.brow, self.n0 * self.w), t))
+            if self.n1:
+                o.append("global_load_%s %s, %%[bo1], %%[bb%d]" % (
+                    width[self.n1 * self.w],
+                    self.reg(self.base(s) + self.xregs + t * self.brow + self.n0 * self.w, self.n1 * self.w), t))
+        for c in range(self.cb):
+            o.append("v_lshl_add_u64 %%[x%d], %%[x%d], 0, %%[xs]" % (c, c))
+        o.append("v_add_u32 %[bo0], %[bs], %[bo0]")
+        if self.n1:
+            o.append("v_add_u32 %[bo1], %[bs], %[bo1]")
+        return o
+
+    def consume(self, s, wait):
+        mfma = "v_mfma_f64_16x16x4_f64" if self.w == 2 else "v_mfma_f32_16x16x4_f32"
+        o = ["s_waitcnt vmcnt(%d)" % wait]
+        for t in range(4):
+            for c in range(self.cb):
+                for j in range(self.jb):
+                    a = "%%[a%d%d]" % (c, j)
+                    o.append("%s %s, %s, %s, %s" % (mfma, a, self.xval(s, c, t), self.bval(s, t, j), a))
+        return o
+
+    def block(self):
+        d, s_n, l = self.d, self.d + 1, self.loads
+        o = ["s_nop 4"]
+        for k in range(d):
+            o += self.issue(k)
+        o.append("1:")
+        for u in range(s_n):
+            o.append("s_cmp_eq_u32 %[n], 0")
+            o.append("s_cbranch_scc1 %df" % (10 + u))
+            o += self.issue((u + d) % s_n)
+            o.append("s_sub_u32 %[n], %[n], 1")
+            o += self.consume(u, d * l)
+        o.append("s_branch 1b")
+        for u in range(s_n):
+            o.append("%d:" % (10 + u))
+            for k in range(d):
+                o += self.consume((u + k) % s_n, (d - 1 - k) * l)
+            if u < s_n - 1:
+                o.append("s_branch 9f")
+        o.append("9:")
+        o += ["s_nop 7", "s_nop 7", "s_nop 7"]
+        return o
+
+    def emit(self):
+        t = self.tag().upper()
+        c = self.ctype()
+        out = "// %s: CB = %d, JB = %d; %d steps in flight, ring of %d sets in v[%d:%d], %d wavefronts per SIMD\n" % (
+            c, self.cb, self.jb, self.d, self.d + 1, self.t0, self.last_reg(), self.waves)
+        out += "#define MTTKRP_ROWS_PIPE_%s_ASM \\\n" % t
+        out += " \\\n".join('    "%s\\n"' % line for line in self.block()) + "\n"
+        clob = ", ".join('"v%d"' % v for v in range(self.t0, self.last_reg() + 1))
+        accs = ", ".join('[a%d%d] "+v"(acc[%d][%d])' % (a, j, a, j) for a in range(self.cb) for j in range(self.jb))
+        outs = ", ".join('[x%d] "+v"(xq[%d])' % (a, a) for a in range(self.cb)) + ', [bo0] "+v"(bo0), ' + \
+               ('[bo1] "+v"(bo1), ' if self.n1 else "") + '[n] "+s"(n_more), ' + accs
+        ins = '[xs] "s"(x_step_bytes), [bs] "s"(b_step_bytes), ' + \
+              ", ".join('[bb%d] "s"(bb[%d])' % (r, r) for r in range(4))
+        out += "template <> struct RowsPipe<%s, %d, %d> {\n" % (c, self.cb, self.jb)
+        out += "    static constexpr bool value = true;\n"
+        out += "    static constexpr int depth = %d;\n    static constexpr int waves = %d;\n" % (self.d, self.waves)
+        out += "    static __device__ __forceinline__ void run(typename Mfma<%s>::acc_t (&acc)[%d][%d], const %s* (&xq)[%d],\n" % (
+            c, self.cb, self.jb, c, self.cb)
+        out += "                                               int64_t x_step_bytes, const %s* const (&bb)[4], uint32_t bo0,\n" % c
+        out += "                                               uint32_t bo1, uint32_t b_step_bytes, int n_more)\n    {\n"
+        if not self.n1:
+            out += "        (void)bo1;\n"
+        out += "        asm volatile(MTTKRP_ROWS_PIPE_%s_ASM : %s : %s : %s, \"scc\", \"memory\");\n" % (t, outs, ins, clob)
+        out += "    }\n};\n\n"
+        return out
+
+
+def main():
+    insts = [Inst(w, cb, jb) for w in (2, 1) for cb, jb in TILES]
+    insts = [i for i in insts if i.budget]
+    out = "// Generated by gen_rows_pipe.py; do not edit.\n"
+    out += "// Primary template: no pipelined run for an instantiation (the kernel then uses its plain loop).\n"
+    out += "template <typename T, int CB, int JB> struct RowsPipe {\n"
+    out += "    static constexpr bool value = false;\n    static constexpr int depth = 1 << 30;\n"
+    out += "    static constexpr int waves = 0;\n"
+    out += "    static __device__ __forceinline__ void run(typename Mfma<T>::acc_t (&)[CB][JB], const T* (&)[CB], int64_t,\n"
+    out += "                                               const T* const (&)[4], uint32_t, uint32_t, uint32_t, int)\n    {\n    }\n};\n\n"
+    for i in insts:
+        out += i.emit()
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "mttkrp_rows_pipe.inc")
+    with open(path, "w") as f:
+        f.write(out)
+    for i in insts:
+        print("%s: acc %3d, set %2d, depth %d, budget %d (%d waves), ring v[%d:%d], loads/step %d" % (
+            i.tag(), i.acc, i.set, i.d, i.budget, i.waves, i.t0, i.last_reg(), i.loads))
+    return path
+
+
+if __name__ == "__main__":
+    print(main())

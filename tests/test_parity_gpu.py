@@ -427,8 +427,8 @@ def test_row_contraction_schedule(mt, oracle, dtype):
             for key in tune:
                 mt.mttkrp_tune_set(key, 0)
         # chosen by the planner itself: few column entries, long mode 0 (2053 rows: a ragged last step)
-        # (k = 1: 12 column entries, either type; k = 2: 40 entries, fp64 at R > 48 only)
-        dims, R = (2053, 40, 12), 50
+        # (k = 1: 12 column entries, either type; k = 2: 40 entries, at R = 30 in fp64 only)
+        dims, R = (2053, 40, 12), 30
         X, A = make_problem(dims, R, dtype, seed=77)
         for k in (1, 2):
             desc = mt.mttkrp_plan_describe(dims, R, k, sb)
