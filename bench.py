@@ -92,7 +92,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path is one GPU's share at its "
-              "real shape; see DESIGN.md for how it would shard). Use --gpus 1.", file=sys.stderr)
+              "real shape; sharding over several GPUs is described in the design notes, not built). Use --gpus 1.", file=sys.stderr)
         return 2
 
     import torch
