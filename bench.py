@@ -183,7 +183,11 @@ def main() -> int:
     roofline["kernel_ms_mean"] = round(kernel_ms, 4)
     roofline["launches_timed"] = len(stream_ms_all)
     roofline["algorithmic_bytes_per_launch"] = alg_bytes
-    roofline["traffic"] = perf_model.measured_traffic(w.name)
+    # HBM bytes per launch from the rocprofv3 counter runs recorded under profiles/ (fetched + written,
+    # each scaled by what the same counter reads for a plain copy of known size), or null
+    detail = perf_model.measured_traffic(w.name)
+    roofline["traffic"] = detail["total_bytes"] if detail else None
+    roofline["traffic_detail"] = detail
 
     x_gbps = w.ndim * w.numel * w.itemsize / (ms_per_step * 1e-3) / 1e9
     out = {
