@@ -191,8 +191,9 @@ int mttkrp_timing_last(float* stream_ms, float* combine_ms);
  *   "max_steps"     upper bound on 4-column steps per work item
  *   "xcd_remap"     1 = contiguous item ranges per XCD, 2 = plain order (default)
  *   "ws_percent"    cap on first-mode partial-sum traffic, percent of X bytes
- *   "max_col_blocks"  16-column blocks of the output per wavefront (1..4); more
- *                   columns are covered by further wavefronts that re-read X
+ *   "max_col_blocks"  16-column blocks of the output per wavefront (1..4; the second
+ *                   schedule up to 8); more columns are covered by further
+ *                   wavefronts that re-read X
  *   "first_group"   first mode only: 4 = the four wavefronts of a workgroup sum
  *                   their tiles in LDS and write one partial tile, 1 = every
  *                   wavefront writes its own partial tile, 0 = chosen per shape

@@ -16,8 +16,8 @@ many younger loads may be outstanding) is the same.
 One step = 16 rows of mode 0: for each of the CB column blocks the lane's four
 tensor rows (fp32: one 16-byte load; fp64: two, 64 bytes apart, so that the four
 lanes of a column read one whole 64-byte sector per load), for each of the four rows t
-the lane's JB entries of that row of A_0 (one or two loads in the wide column
-layout `Lay` of mttkrp.hip), and 4 * CB * JB 16x16x4 MFMAs: MFMA (t, cb, jb) takes
+the lane's JB entries of that row of A_0 (one load per chunk of the wide column
+layout of mttkrp.hip, up to four), and 4 * CB * JB 16x16x4 MFMAs: MFMA (t, cb, jb) takes
 row t of column block cb and of output column block jb.  The tensor pointers (one
 per column block, per lane) advance by 16 rows, the byte offsets into A_0 (per
 lane, relative to four wave-uniform row pointers) by 16 rows of A_0.
@@ -30,7 +30,8 @@ import os
 D_MAX = int(os.environ.get("MTTKRP_GEN_ROWS_DEPTH", "3"))
 OTHERS = {2: 46, 1: 44}      # registers the rest of the kernel keeps live across a run (fp64, fp32)
 X_FLAGS = os.environ.get("MTTKRP_GEN_ROWS_XFLAGS", "")   # cache policy of the tensor loads (experiments), e.g. " nt"
-TILES = [(1, 1), (1, 2), (1, 3), (1, 4), (2, 1), (2, 2), (2, 3), (2, 4), (3, 1), (3, 2), (4, 1), (4, 2)]
+TILES = [(1, 1), (1, 2), (1, 3), (1, 4), (1, 5), (1, 6), (1, 7), (1, 8),
+         (2, 1), (2, 2), (2, 3), (2, 4), (3, 1), (3, 2), (4, 1), (4, 2)]
 
 
 class Inst:
@@ -42,10 +43,10 @@ class Inst:
         self.set = self.xregs + self.bregs
         self.acc = cb * jb * 4 * w
         g = 16 // (4 * w)                               # values per 16-byte load
-        self.n0 = min(jb, g)
-        self.n1 = jb - self.n0
+        self.chunks = [min(g, jb - g * ch) for ch in range((jb + g - 1) // g)]   # blocks per chunk of output columns
+        self.g = g
         self.xloads = w                                 # load instructions per column block
-        self.loads = cb * self.xloads + 4 * (1 + (1 if self.n1 else 0))
+        self.loads = cb * self.xloads + 4 * len(self.chunks)
         self.pick()
 
     def ring(self, d):
@@ -97,17 +98,14 @@ class Inst:
                 o.append("global_load_dwordx4 %s, %%[x%d], off%s" % (
                     self.reg(self.base(s) + c * 4 * self.w + 4 * h, 4), c, (" offset:64" if h else "") + X_FLAGS))
         for t in range(4):
-            o.append("global_load_%s %s, %%[bo0], %%[bb%d]" % (
-                width[self.n0 * self.w], self.reg(self.base(s) + self.xregs + t * self.brow, self.n0 * self.w), t))
-            if self.n1:
-                o.append("global_load_%s %s, %%[bo1], %%[bb%d]" % (
-                    width[self.n1 * self.w],
-                    self.reg(self.base(s) + self.xregs + t * self.brow + self.n0 * self.w, self.n1 * self.w), t))
+            for ch, n in enumerate(self.chunks):
+                o.append("global_load_%s %s, %%[bo%d], %%[bb%d]" % (
+                    width[n * self.w],
+                    self.reg(self.base(s) + self.xregs + t * self.brow + ch * self.g * self.w, n * self.w), ch, t))
         for c in range(self.cb):
             o.append("v_lshl_add_u64 %%[x%d], %%[x%d], 0, %%[xs]" % (c, c))
-        o.append("v_add_u32 %[bo0], %[bs], %[bo0]")
-        if self.n1:
-            o.append("v_add_u32 %[bo1], %[bs], %[bo1]")
+        for ch in range(len(self.chunks)):
+            o.append("v_add_u32 %%[bo%d], %%[bs], %%[bo%d]" % (ch, ch))
         return o
 
     def consume(self, s, wait):
@@ -152,8 +150,8 @@ class Inst:
         out += " \\\n".join('    "%s\\n"' % line for line in self.block()) + "\n"
         clob = ", ".join('"v%d"' % v for v in range(self.t0, self.last_reg() + 1))
         accs = ", ".join('[a%d%d] "+v"(acc[%d][%d])' % (a, j, a, j) for a in range(self.cb) for j in range(self.jb))
-        outs = ", ".join('[x%d] "+v"(xq[%d])' % (a, a) for a in range(self.cb)) + ', [bo0] "+v"(bo0), ' + \
-               ('[bo1] "+v"(bo1), ' if self.n1 else "") + '[n] "+s"(n_more), ' + accs
+        outs = ", ".join('[x%d] "+v"(xq[%d])' % (a, a) for a in range(self.cb)) + ", " + \
+               ", ".join('[bo%d] "+v"(bo[%d])' % (ch, ch) for ch in range(len(self.chunks))) + ', [n] "+s"(n_more), ' + accs
         ins = '[xs] "s"(x_step_bytes), [bs] "s"(b_step_bytes), ' + \
               ", ".join('[bb%d] "s"(bb[%d])' % (r, r) for r in range(4))
         out += "template <> struct RowsPipe<%s, %d, %d> {\n" % (c, self.cb, self.jb)
@@ -161,10 +159,9 @@ class Inst:
         out += "    static constexpr int depth = %d;\n    static constexpr int waves = %d;\n" % (self.d, self.waves)
         out += "    static __device__ __forceinline__ void run(typename Mfma<%s>::acc_t (&acc)[%d][%d], const %s* (&xq)[%d],\n" % (
             c, self.cb, self.jb, c, self.cb)
-        out += "                                               int64_t x_step_bytes, const %s* const (&bb)[4], uint32_t bo0,\n" % c
-        out += "                                               uint32_t bo1, uint32_t b_step_bytes, int n_more)\n    {\n"
-        if not self.n1:
-            out += "        (void)bo1;\n"
+        out += "                                               int64_t x_step_bytes, const %s* const (&bb)[4], uint32_t (&bo)[%d],\n" % (
+            c, len(self.chunks))
+        out += "                                               uint32_t b_step_bytes, int n_more)\n    {\n"
         out += "        asm volatile(MTTKRP_ROWS_PIPE_%s_ASM : %s : %s : %s, \"scc\", \"memory\");\n" % (t, outs, ins, clob)
         out += "    }\n};\n\n"
         return out
@@ -179,7 +176,7 @@ def main():
     out += "    static constexpr bool value = false;\n    static constexpr int depth = 1 << 30;\n"
     out += "    static constexpr int waves = 0;\n"
     out += "    static __device__ __forceinline__ void run(typename Mfma<T>::acc_t (&)[CB][JB], const T* (&)[CB], int64_t,\n"
-    out += "                                               const T* const (&)[4], uint32_t, uint32_t, uint32_t, int)\n    {\n    }\n};\n\n"
+    out += "                                               const T* const (&)[4], uint32_t (&)[(JB * (int)sizeof(T) + 15) / 16], uint32_t, int)\n    {\n    }\n};\n\n"
     for i in insts:
         out += i.emit()
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "mttkrp_rows_pipe.inc")
