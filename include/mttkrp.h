@@ -15,7 +15,9 @@
  * adjacent modes are treated as one (two short column modes; modes 0 and 1 when
  * I_0 fits the 16-row MFMA blocks badly), the row-wise product of their two
  * factors, which is only formed while it stays below a constant size (8 MiB by
- * default; at most two such matrices per call).
+ * default; at most two such matrices per call), or, for k != 0 with at most
+ * 1024 entries in the modes other than 0 and k, the product of those modes'
+ * factor rows (at most 1024 x R values).
  *
  * Layouts (Sec. II-A: ind2sub/sub2ind "defined like MATLAB" => first index
  * fastest; Sec. III: row-wise factor layout):
