@@ -203,7 +203,8 @@ class Inst:
         return out
 
 
-def main():
+def main(path=None):
+    """Writes the include file (next to this script unless a path is given) and returns its path."""
     insts = [Inst(w, rb, jb) for w in (2, 1) for rb in (1, 2, 3, 4) for jb in (1, 2, 3, 4)]
     insts = [i for i in insts if i.budget]
     if ONLY:
@@ -219,7 +220,8 @@ def main():
     out += "                                               const T*, uint32_t, uint32_t, uint32_t, const T (&)[JB], int)\n    {\n    }\n};\n\n"
     for i in insts:
         out += i.emit()
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "mttkrp_pipe.inc")
+    if path is None:
+        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "mttkrp_pipe.inc")
     with open(path, "w") as f:
         f.write(out)
     for i in insts:

@@ -167,7 +167,8 @@ class Inst:
         return out
 
 
-def main():
+def main(path=None):
+    """Writes the include file (next to this script unless a path is given) and returns its path."""
     insts = [Inst(w, cb, jb) for w in (2, 1) for cb, jb in TILES]
     insts = [i for i in insts if i.budget]
     out = "// Generated by gen_rows_pipe.py; do not edit.\n"
@@ -179,7 +180,8 @@ def main():
     out += "                                               const T* const (&)[4], uint32_t (&)[(JB * (int)sizeof(T) + 15) / 16], uint32_t, int)\n    {\n    }\n};\n\n"
     for i in insts:
         out += i.emit()
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "mttkrp_rows_pipe.inc")
+    if path is None:
+        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "mttkrp_rows_pipe.inc")
     with open(path, "w") as f:
         f.write(out)
     for i in insts:
