@@ -14,13 +14,24 @@ budget, exit check per step, one drain tail per ring position, waits that name h
 many younger loads may be outstanding) is the same.
 
 One step = 16 rows of mode 0: for each of the CB column blocks the lane's four
-tensor rows (fp32: one 16-byte load; fp64: two, 64 bytes apart, so that the four
-lanes of a column read one whole 64-byte sector per load), for each of the four rows t
+tensor rows 4 kq .. 4 kq + 3 of its column (fp32: one 16-byte load; fp64: see
+below), for each of the four rows t
 the lane's JB entries of that row of A_0 (one load per chunk of the wide column
 layout of mttkrp.hip, up to four), and 4 * CB * JB 16x16x4 MFMAs: MFMA (t, cb, jb) takes
 row t of column block cb and of output column block jb.  The tensor pointers (one
 per column block, per lane) advance by 16 rows, the byte offsets into A_0 (per
 lane, relative to four wave-uniform row pointers) by 16 rows of A_0.
+
+fp64 tensor loads.  A lane needs 32 bytes of its column's 128-byte line, and the
+MFMA layout gives a column only four lanes, so no single load can read a whole line
+into place; two loads that each read half of every line make the second depend on
+the line staying cached, which fails when the 16 columns lie a large power of two
+apart and evict each other from one cache set.  Instead the two lanes of an
+even/odd column pair (same kq) work together: load 0 reads the even column's line
+with the pair's eight lanes (lane e = 0, 1 of the pair takes 16-byte piece 2 kq + e),
+load 1 the odd column's line likewise, so every load reads whole lines of eight
+columns; then the two lanes exchange, within the wavefront (one DPP move per
+register), the pieces that belong to the other's column.
 
 Run by build.py before hipcc; the output is committed so that the library also
 builds without running this script.
@@ -28,7 +39,7 @@ builds without running this script.
 import os
 
 D_MAX = int(os.environ.get("MTTKRP_GEN_ROWS_DEPTH", "3"))
-OTHERS = {2: 46, 1: 44}      # registers the rest of the kernel keeps live across a run (fp64, fp32)
+OTHERS = {2: 40, 1: 44}      # registers the rest of the kernel keeps live across a run (fp64, fp32)
 X_FLAGS = os.environ.get("MTTKRP_GEN_ROWS_XFLAGS", "")   # cache policy of the tensor loads (experiments), e.g. " nt"
 TILES = [(1, 1), (1, 2), (1, 3), (1, 4), (1, 5), (1, 6), (1, 7), (1, 8),
          (2, 1), (2, 2), (2, 3), (2, 4), (3, 1), (3, 2), (4, 1), (4, 2)]
@@ -46,11 +57,12 @@ class Inst:
         self.chunks = [min(g, jb - g * ch) for ch in range((jb + g - 1) // g)]   # blocks per chunk of output columns
         self.g = g
         self.xloads = w                                 # load instructions per column block
+        self.swz = w == 2                               # fp64: whole-line loads by column pairs + exchange
         self.loads = cb * self.xloads + 4 * len(self.chunks)
         self.pick()
 
     def ring(self, d):
-        return self.set * (d + 1)
+        return self.set * (d + 1) + (4 if self.w == 2 else 0)     # fp64: four temporaries of the exchange
 
     def pick(self):
         # the most wavefronts per SIMD for which at least two steps in flight fit, else one step at two wavefronts
@@ -89,21 +101,29 @@ class Inst:
     def last_reg(self):
         return self.t0 + self.ring(self.d) - 1
 
+    @property
+    def tmp(self):
+        return self.t0 + self.set * (self.d + 1)
+
     # --- code
     def issue(self, s):
         o = []
         width = {1: "dword", 2: "dwordx2", 3: "dwordx3", 4: "dwordx4"}
         for c in range(self.cb):
-            for h in range(self.xloads):
-                o.append("global_load_dwordx4 %s, %%[x%d], off%s" % (
-                    self.reg(self.base(s) + c * 4 * self.w + 4 * h, 4), c, (" offset:64" if h else "") + X_FLAGS))
+            if self.swz:
+                for h in range(2):      # h = 0: the pair's even column, h = 1: its odd column
+                    o.append("global_load_dwordx4 %s, %%[x%d%s], off%s" % (
+                        self.reg(self.base(s) + c * 8 + 4 * h, 4), c, "ab"[h], X_FLAGS))
+            else:
+                o.append("global_load_dwordx4 %s, %%[x%d], off%s" % (self.reg(self.base(s) + c * 4, 4), c, X_FLAGS))
         for t in range(4):
             for ch, n in enumerate(self.chunks):
                 o.append("global_load_%s %s, %%[bo%d], %%[bb%d]" % (
                     width[n * self.w],
                     self.reg(self.base(s) + self.xregs + t * self.brow + ch * self.g * self.w, n * self.w), ch, t))
         for c in range(self.cb):
-            o.append("v_lshl_add_u64 %%[x%d], %%[x%d], 0, %%[xs]" % (c, c))
+            for nm in (["x%da" % c, "x%db" % c] if self.swz else ["x%d" % c]):
+                o.append("v_lshl_add_u64 %%[%s], %%[%s], 0, %%[xs]" % (nm, nm))
         for ch in range(len(self.chunks)):
             o.append("v_add_u32 %%[bo%d], %%[bs], %%[bo%d]" % (ch, ch))
         return o
@@ -111,6 +131,25 @@ class Inst:
     def consume(self, s, wait):
         mfma = "v_mfma_f64_16x16x4_f64" if self.w == 2 else "v_mfma_f32_16x16x4_f32"
         o = ["s_waitcnt vmcnt(%d)" % wait]
+        if self.swz:
+            # vcc = odd lanes (e = 1).  Per register r of the two loads H0 (even column), H1 (odd
+            # column): send what belongs to the partner (e = 0 sends H1, e = 1 sends H0), swap it
+            # between the two lanes, then H0 := piece 2 kq (rows 4 kq, 4 kq + 1) and H1 := piece
+            # 2 kq + 1 (rows 4 kq + 2, 4 kq + 3) of the lane's own column.
+            for c in range(self.cb):
+                h0 = self.base(s) + c * 8
+                h1 = h0 + 4
+                for r in range(4):
+                    o.append("v_cndmask_b32 v%d, v%d, v%d, vcc" % (self.tmp + r, h1 + r, h0 + r))
+                o.append("s_nop 1")
+                for r in range(4):
+                    o.append("v_mov_b32_dpp v%d, v%d quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf" % (
+                        self.tmp + r, self.tmp + r))
+                o.append("s_nop 1")
+                for r in range(4):
+                    o.append("v_cndmask_b32 v%d, v%d, v%d, vcc" % (h0 + r, h0 + r, self.tmp + r))
+                    o.append("v_cndmask_b32 v%d, v%d, v%d, vcc" % (h1 + r, self.tmp + r, h1 + r))
+            o.append("s_nop 1")
         for t in range(4):
             for c in range(self.cb):
                 for j in range(self.jb):
@@ -121,6 +160,8 @@ class Inst:
     def block(self):
         d, s_n, l = self.d, self.d + 1, self.loads
         o = ["s_nop 4"]
+        if self.swz:
+            o = ["s_mov_b32 vcc_lo, 0xaaaaaaaa", "s_mov_b32 vcc_hi, 0xaaaaaaaa", "s_nop 4"]
         for k in range(d):
             o += self.issue(k)
         o.append("1:")
@@ -150,19 +191,26 @@ class Inst:
         out += " \\\n".join('    "%s\\n"' % line for line in self.block()) + "\n"
         clob = ", ".join('"v%d"' % v for v in range(self.t0, self.last_reg() + 1))
         accs = ", ".join('[a%d%d] "+v"(acc[%d][%d])' % (a, j, a, j) for a in range(self.cb) for j in range(self.jb))
-        outs = ", ".join('[x%d] "+v"(xq[%d])' % (a, a) for a in range(self.cb)) + ", " + \
+        if self.swz:
+            xops = ", ".join('[x%da] "+v"(xq[%d]), [x%db] "+v"(xq[%d])' % (a, 2 * a, a, 2 * a + 1) for a in range(self.cb))
+        else:
+            xops = ", ".join('[x%d] "+v"(xq[%d])' % (a, a) for a in range(self.cb))
+        outs = xops + ", " + \
                ", ".join('[bo%d] "+v"(bo[%d])' % (ch, ch) for ch in range(len(self.chunks))) + ', [n] "+s"(n_more), ' + accs
         ins = '[xs] "s"(x_step_bytes), [bs] "s"(b_step_bytes), ' + \
               ", ".join('[bb%d] "s"(bb[%d])' % (r, r) for r in range(4))
         out += "template <> struct RowsPipe<%s, %d, %d> {\n" % (c, self.cb, self.jb)
         out += "    static constexpr bool value = true;\n"
         out += "    static constexpr int depth = %d;\n    static constexpr int waves = %d;\n" % (self.d, self.waves)
+        out += "    static constexpr int xptrs = %d;         // tensor pointers per lane: one per column block, or two (column pair)\n" % (
+            self.cb * (2 if self.swz else 1))
         out += "    static __device__ __forceinline__ void run(typename Mfma<%s>::acc_t (&acc)[%d][%d], const %s* (&xq)[%d],\n" % (
-            c, self.cb, self.jb, c, self.cb)
+            c, self.cb, self.jb, c, self.cb * (2 if self.swz else 1))
         out += "                                               int64_t x_step_bytes, const %s* const (&bb)[4], uint32_t (&bo)[%d],\n" % (
             c, len(self.chunks))
         out += "                                               uint32_t b_step_bytes, int n_more)\n    {\n"
-        out += "        asm volatile(MTTKRP_ROWS_PIPE_%s_ASM : %s : %s : %s, \"scc\", \"memory\");\n" % (t, outs, ins, clob)
+        out += "        asm volatile(MTTKRP_ROWS_PIPE_%s_ASM : %s : %s : %s, \"scc\", %s\"memory\");\n" % (
+            t, outs, ins, clob, '\"vcc\", ' if self.swz else "")
         out += "    }\n};\n\n"
         return out
 
@@ -175,7 +223,7 @@ def main(path=None):
     out += "// Primary template: no pipelined run for an instantiation (the kernel then uses its plain loop).\n"
     out += "template <typename T, int CB, int JB> struct RowsPipe {\n"
     out += "    static constexpr bool value = false;\n    static constexpr int depth = 1 << 30;\n"
-    out += "    static constexpr int waves = 0;\n"
+    out += "    static constexpr int waves = 0;\n    static constexpr int xptrs = CB;\n"
     out += "    static __device__ __forceinline__ void run(typename Mfma<T>::acc_t (&)[CB][JB], const T* (&)[CB], int64_t,\n"
     out += "                                               const T* const (&)[4], uint32_t (&)[(JB * (int)sizeof(T) + 15) / 16], uint32_t, int)\n    {\n    }\n};\n\n"
     for i in insts:
