@@ -205,9 +205,9 @@ int mttkrp_timing_last(float* stream_ms, float* combine_ms);
  *   "fuse_bytes"    largest product matrix (bytes) for which two adjacent modes
  *                   are fused into one (default 8 MiB; 1 = never fuse)
  *   "contract_rows" schedule for k != 0: 1 = contract over mode 0 (rows) whenever the
- *                   other modes' entries number at most 1024, 2 = never, 0 = in fp64 with
- *                   R > 48 when those are few (under 256) and mode 0 is at least eight
- *                   times as long
+ *                   other modes' entries number at most 1024, 2 = never, 0 = chosen by
+ *                   the planner (those entries few, under 128, mode 0 at least eight
+ *                   times as long, and R large enough for the data type)
  *   "rows_col_blocks"  that schedule only: 16-entry blocks of the column space per
  *                   wavefront (1..4), 0 = chosen by the planner
  *   "inner_splits"  pieces the sweep over the inner column mode is cut into (1..64),
