@@ -5,6 +5,10 @@ the benchmark's CPU-baseline leg may import this module.  It holds argument
 marshalling and the comparison norm; the arithmetic is in the C file, which
 follows the element-wise MTTKRP definition (paper Sec. II-B, Eq. (elem), with
 lambda = 1).  Nothing here imports the HIP package.
+
+Parity status: pinned.  The C routine by tests/test_oracle_pins.py; the two
+error measures below (through which every parity assertion goes) by
+hand-computed values and planted mistakes in tests/test_comparator_pins.py.
 """
 from __future__ import annotations
 
@@ -149,3 +153,29 @@ def normwise_rel_err(M_test: np.ndarray, M_ref: np.ndarray) -> float:
     if den == 0:
         return 0.0 if num == 0 else float("inf")
     return float(num / den)
+
+
+def rowwise_rel_err(M_test: np.ndarray, M_ref: np.ndarray) -> float:
+    """max over output rows n of ||M_test[n] - M_ref[n]||_2 / ||M_ref[n]||_2.
+
+    The normwise error above can hide one wrong row of small norm under the
+    norm of the whole matrix; row n of the result depends only on subtensor
+    S_n^(k) (Sec. III), so every row is also held to the tolerance on its own.
+    A row whose reference is all zero must be all zero (else inf).
+    """
+    a = np.asarray(M_test, dtype=np.longdouble)
+    b = np.asarray(M_ref, dtype=np.longdouble)
+    if a.shape != b.shape or a.ndim != 2:
+        raise ValueError("need two matrices of one shape, got %s and %s" % (a.shape, b.shape))
+    num = np.sqrt(np.sum((a - b) ** 2, axis=1))
+    den = np.sqrt(np.sum(b ** 2, axis=1))
+    worst = 0.0
+    for n in range(a.shape[0]):
+        if den[n] == 0:
+            e = 0.0 if num[n] == 0 else float("inf")
+        else:
+            e = float(num[n] / den[n])
+        if e != e:              # NaN: no later row may hide it
+            return float("nan")
+        worst = max(worst, e)
+    return worst
