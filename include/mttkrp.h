@@ -10,8 +10,12 @@
  *
  * which equals X_(k) * (A_d (.) ... (.) A_{k+1} (.) A_{k-1} (.) ... (.) A_1) of
  * Eq. (krp) without ever forming the Khatri-Rao matrix or an unfolded or
- * permuted copy of X.  Extra device memory is O(R * sum_n I_n)-class partial
- * sums (Sec. I, contributions; Sec. II-B last paragraph) plus, where two
+ * permuted copy of X.  Extra device memory is partial sums in the
+ * O(R * sum_n I_n) class of Sec. I (contributions) and Sec. II-B (last
+ * paragraph): slots * I_k * R values with slots a plan constant, never more
+ * than 5 % of the bytes of X or 64 MiB, whichever is larger (one exception:
+ * fp32 with I_0 < 16 and R >= 500, where short accumulation chains force many
+ * splits and the partial sums can reach 10 to 40 % of X); plus, where two
  * adjacent modes are treated as one (two short column modes; modes 0 and 1 when
  * I_0 fits the 16-row MFMA blocks badly), the row-wise product of their two
  * factors, which is only formed while it stays below a constant size (8 MiB by
@@ -44,9 +48,9 @@
  *   MTTKRP_ERR_INVALID_ARG  null X/M/dims/factors, null factors[m != k],
  *                           ndim < 2, dims[m] < 1, R < 1, k out of range,
  *                           element count or byte size overflowing int64
- *   MTTKRP_ERR_UNSUPPORTED  ndim > MTTKRP_MAX_NDIM, a dimension or R >= 2^31,
- *                           or a decomposition that would need >= 2^31 work
- *                           items
+ *   MTTKRP_ERR_UNSUPPORTED  ndim > MTTKRP_MAX_NDIM, a dimension >= 2^31,
+ *                           R >= 2^27, or a decomposition that would need
+ *                           >= 2^31 work items
  *   MTTKRP_ERR_WORKSPACE    a *_ws call with too few workspace bytes, or
  *                           workspace not 256-byte aligned
  *   MTTKRP_ERR_DEVICE       a HIP runtime call failed
@@ -73,9 +77,15 @@ typedef enum {
 
 /*
  * Core calls, Eq. (elem): M = X_(k) (Khatri-Rao of all A_m, m != k), one per
- * data type.  Partial sums live in a library-owned per-device workspace that
- * grows on demand; growing it is the only time these calls allocate (and
- * synchronise the device).
+ * data type.  Partial sums live in a library-owned workspace per (device,
+ * stream) that grows on demand, so calls in flight on different streams of one
+ * device do not share scratch memory and may overlap freely; calls on one
+ * stream are ordered by the stream.  Growing a workspace is the only time these
+ * calls allocate; they then wait on the host for the last call that used it.
+ * A device keeps the workspaces of the eight most recently used streams; a
+ * ninth stream takes over the least recently used one after waiting for that
+ * stream's last call.  Not for use under stream capture (the calls record an
+ * event they may later wait on): capture the *_ws calls instead.
  *   ndim     number of modes d, 2 <= d <= MTTKRP_MAX_NDIM
  *   dims     host array of d extents I_0..I_{d-1}, each >= 1
  *   X        device, prod(dims) values

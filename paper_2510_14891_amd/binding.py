@@ -13,8 +13,7 @@ import os
 from typing import Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# MTTKRP_LIB selects another build of the same library (tuning experiments)
-LIB_PATH = os.environ.get("MTTKRP_LIB") or os.path.join(_HERE, "libmttkrp_hip.so")
+LIB_PATH = os.path.join(_HERE, "libmttkrp_hip.so")
 
 MTTKRP_OK = 0
 MTTKRP_ERR_INVALID_ARG = 1

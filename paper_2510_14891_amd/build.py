@@ -31,7 +31,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
                                              os.path.getmtime(os.path.join(HERE, "csrc", "gen_pipe.py")),
                                              os.path.getmtime(os.path.join(HERE, "csrc", "gen_rows_pipe.py")))):
         return LIB
-    # regenerate the inline-assembly include (deterministic; the result is committed too)
+    # write the inline-assembly includes (deterministic build products of the two generators)
     for gen in ("gen_pipe.py", "gen_rows_pipe.py"):
         subprocess.run([sys.executable, os.path.join(HERE, "csrc", gen)], check=True, stdout=subprocess.DEVNULL)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

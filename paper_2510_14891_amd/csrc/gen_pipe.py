@@ -28,15 +28,14 @@ registers = 4 / 3 / 2 wavefronts per SIMD) and the depth D: the most
 wavefronts for which accumulators + ring + an allowance for everything else the
 kernel keeps live still fit, with 3 <= D <= 5.
 
-Run by build.py before hipcc; the output is committed so that the library also
-builds without running this script.
+Run by build.py before hipcc on every build; the output is a build product and is
+not kept under version control.
 """
 import os
 
-D_MAX = int(os.environ.get("MTTKRP_GEN_DEPTH", "5"))
-D_MIN = int(os.environ.get("MTTKRP_GEN_DEPTH_MIN", "3"))
+D_MAX = 5
+D_MIN = 3
 OTHERS = {2: 60, 1: 56}      # registers the rest of the kernel keeps live across a run (fp64, fp32)
-ONLY = os.environ.get("MTTKRP_GEN_ONLY", "")   # e.g. "d42,f34": restrict the instantiations (experiments)
 
 
 def even(n):
@@ -207,9 +206,6 @@ def main(path=None):
     """Writes the include file (next to this script unless a path is given) and returns its path."""
     insts = [Inst(w, rb, jb) for w in (2, 1) for rb in (1, 2, 3, 4) for jb in (1, 2, 3, 4)]
     insts = [i for i in insts if i.budget]
-    if ONLY:
-        keep = set(ONLY.split(","))
-        insts = [i for i in insts if i.tag() in keep]
     out = "// Generated by gen_pipe.py; do not edit.\n"
     out += "// Primary template: no pipelined run for an instantiation (the kernel then uses batches only).\n"
     out += "template <typename T, int RB, int JB> struct Pipe {\n"

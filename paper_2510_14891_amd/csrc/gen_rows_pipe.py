@@ -33,14 +33,14 @@ load 1 the odd column's line likewise, so every load reads whole lines of eight
 columns; then the two lanes exchange, within the wavefront (one DPP move per
 register), the pieces that belong to the other's column.
 
-Run by build.py before hipcc; the output is committed so that the library also
-builds without running this script.
+Run by build.py before hipcc on every build; the output is a build product and is
+not kept under version control.
 """
 import os
 
-D_MAX = int(os.environ.get("MTTKRP_GEN_ROWS_DEPTH", "3"))
+D_MAX = 3
 OTHERS = {2: 40, 1: 44}      # registers the rest of the kernel keeps live across a run (fp64, fp32)
-X_FLAGS = os.environ.get("MTTKRP_GEN_ROWS_XFLAGS", "")   # cache policy of the tensor loads (experiments), e.g. " nt"
+X_FLAGS = ""                 # cache policy of the tensor loads (plain: cache-bypassing flags measured slower)
 TILES = [(1, 1), (1, 2), (1, 3), (1, 4), (1, 5), (1, 6), (1, 7), (1, 8),
          (2, 1), (2, 2), (2, 3), (2, 4), (3, 1), (3, 2), (4, 1), (4, 2)]
 

@@ -248,6 +248,24 @@ def _fill_cp_noise(flat: torch.Tensor, w: Workload) -> None:
         flat[i * L:(i + 1) * L] = (slab + (rel * rms) * noise).to(flat.dtype)
 
 
+def kruskal_tensor(dims: Sequence[int], S: int, seed: int, device="cpu"):
+    """(flat X, [U_0, ..., U_{d-1}]): the rank-S Kruskal tensor (Sec. II-A)
+    X(i) = sum_s prod_m U_m(i_m, s) with N(0,1) factors U_m (I_m x S, seeds
+    seed + m), fp64, flat and first index fastest.  Built slab by slab over the
+    last mode (plain elementwise products and a sum over s, every operation rounded)."""
+    dims = tuple(int(v) for v in dims)
+    d = len(dims)
+    U = [normal(seed + m, (I, S), dtype=torch.float64, device=device) for m, I in enumerate(dims)]
+    Z = U[0]
+    for m in range(1, d - 1):
+        Z = (U[m][:, None, :] * Z[None, :, :]).reshape(-1, S)
+    L = Z.shape[0]
+    flat = torch.empty(L * dims[-1], dtype=torch.float64, device=device)
+    for i in range(dims[-1]):
+        torch.sum(Z * U[-1][i], dim=1, out=flat[i * L:(i + 1) * L])
+    return flat, U
+
+
 def make_tensor(w: Workload, device="cpu") -> torch.Tensor:
     """The dense tensor as a flat 1-D torch tensor of N values, first index
     fastest, seed 1000 + c."""

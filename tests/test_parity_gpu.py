@@ -270,6 +270,31 @@ def test_non_default_stream(mt, oracle):
     assert oracle.normwise_rel_err(M.cpu().numpy(), ref) <= 1e-12
 
 
+def test_calls_in_flight_on_several_streams(mt, oracle):
+    """Core calls (library-owned workspace) enqueued back to back on different streams without
+    any synchronisation between them: every stream has partial sums of its own, so the results
+    of problems that run concurrently all match the oracle.  Ten streams, more than the
+    library keeps workspaces for, so workspaces also change hands."""
+    probs = []
+    # first-mode problems with many partial slots, long enough to overlap on the GPU
+    for i in range(10):
+        dims, R = (96 + 16 * (i % 3), 300 + 7 * i, 257 - 3 * i), 32
+        X, A = make_problem(dims, R, torch.float64, seed=700 + i)
+        k = i % 3
+        probs.append((dims, k, X.cuda(), [a.cuda() for a in A], oracle_mttkrp(oracle, X, dims, A, k)))
+    streams = [torch.cuda.Stream() for _ in probs]
+    torch.cuda.synchronize()
+    outs = [None] * len(probs)
+    for rep in range(3):
+        for i, (dims, k, Xd, Ad, _) in enumerate(probs):
+            with torch.cuda.stream(streams[i]):
+                outs[i] = mt.mttkrp_dense(Xd, dims, Ad, k)
+    torch.cuda.synchronize()
+    for i, (dims, k, _, _, ref) in enumerate(probs):
+        err = oracle.normwise_rel_err(outs[i].cpu().numpy(), ref)
+        assert err <= 1e-12, (i, dims, k, err)
+
+
 # ---------------------------------------------------------------- extended calls and high rank
 @pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
 def test_ex_lambda_and_beta(mt, oracle, dtype):
@@ -305,7 +330,7 @@ def test_ex_lambda_and_beta(mt, oracle, dtype):
         assert oracle.normwise_rel_err(Mn.cpu().numpy(), ref) <= TOL[dtype]
 
 
-@pytest.mark.parametrize("R", [500, 1000])
+@pytest.mark.parametrize("R", [500, 1000, 2000])
 def test_high_rank(mt, oracle, R):
     """The paper's flagship regime (Sec. IV: R = 500 ... 2000): many 64-column chunks."""
     dims = (70, 20, 12, 9)
