@@ -165,6 +165,34 @@ int mttkrp_dense_f32_ld(int ndim, const int64_t* dims, const float* X,
                         const float* lambda, float beta, float* M, int64_t ldM,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * mttkrp_dense_f64 for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same operation, arguments, layouts and errors as mttkrp_dense_f64, and the
+ * same kernels; the partial sums (and the small product matrices of fused
+ * modes) go to a fixed 64 MiB scratch array that is part of the library's
+ * code object, so the call never calls hipMalloc / hipFree or any allocating
+ * routine, and records no timing events (the measurement hooks ignore it).
+ *   - Limit: shapes whose plan needs more than 64 MiB of workspace
+ *     (mttkrp_dense_workspace_bytes(...) > 67108864) return
+ *     MTTKRP_ERR_WORKSPACE and enqueue nothing.  Every benchmark
+ *     configuration fits (the largest, 16384 x 2048 x 64 at R = 128, needs
+ *     exactly 64 MiB).
+ *   - Every GPU the library runs on holds its own copy of the array until the
+ *     process ends.  The first call on a device looks up the array's address
+ *     on that device (and makes the runtime load the code object there): make
+ *     that first call outside graph capture.
+ *   - Nothing in the array has to start at zero: every partial sum that a call
+ *     reads was written by the same call, so the previous call's contents do
+ *     not matter.
+ *   - All calls on one GPU share the one array: calls that overlap on a GPU
+ *     (different streams, or graphs replayed concurrently) race.  Order them.
+ * MTTKRP_ERR_DEVICE when the address lookup fails.
+ */
+int mttkrp_dense_f64_noalloc(int ndim, const int64_t* dims, const double* X,
+                             const double* const* factors, int R, int k, double* M,
+                             void* stream);
+
 /* Static, human-readable text for a status code. */
 const char* mttkrp_status_string(int status);
 

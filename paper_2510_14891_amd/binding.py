@@ -33,7 +33,7 @@ EXPORTED = (
     "mttkrp_ablation_f64", "mttkrp_ablation_f32", "mttkrp_tile_volume",
     "mttkrp_dense_all_modes_f64", "mttkrp_dense_all_modes_f32", "mttkrp_cpals_f64",
     "mttkrp_calibrate_stream", "mttkrp_calibrate_mfma",
-    "mttkrp_dense_f64_ld", "mttkrp_dense_f32_ld",
+    "mttkrp_dense_f64_ld", "mttkrp_dense_f32_ld", "mttkrp_dense_f64_noalloc",
 )
 
 MTTKRP_SCHEDULE_ELEM = 1
@@ -64,7 +64,7 @@ def lib() -> ctypes.CDLL:
     core = [ctypes.c_int, i64p, ctypes.c_void_p, vpp, ctypes.c_int, ctypes.c_int,
             ctypes.c_void_p, ctypes.c_void_p]
     core_ws = core[:-1] + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
-    for name in ("mttkrp_dense_f64", "mttkrp_dense_f32"):
+    for name in ("mttkrp_dense_f64", "mttkrp_dense_f32", "mttkrp_dense_f64_noalloc"):
         getattr(L, name).restype = ctypes.c_int
         getattr(L, name).argtypes = core
     for name in ("mttkrp_dense_f64_ws", "mttkrp_dense_f32_ws"):
@@ -298,6 +298,22 @@ def mttkrp_dense(X, dims: Sequence[int], factors: Sequence, k: int, M=None,
                 d, _dims_array(dims), X.data_ptr(), ptrs, R, int(k), M.data_ptr(),
                 workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                 ctypes.c_void_p(stream))
+    _check(rc)
+    return M
+
+
+def mttkrp_dense_noalloc(X, dims: Sequence[int], factors: Sequence, k: int, M, stream: Optional[int] = None):
+    """mttkrp_dense_f64_noalloc: the fp64 MTTKRP into the caller's ``M`` with the library's fixed
+    scratch array as workspace (no device allocation; see include/mttkrp.h for the limit)."""
+    import torch
+    if X.dtype != torch.float64:
+        raise TypeError("the no-allocation entry point is float64 only")
+    if M is None:
+        raise ValueError("M must be given: this entry point allocates nothing")
+    suffix, d, ptrs, R, M, stream = _marshal(X, dims, factors, k, M, stream)
+    with torch.cuda.device(X.device):
+        rc = lib().mttkrp_dense_f64_noalloc(d, _dims_array(dims), X.data_ptr(), ptrs, R, int(k), M.data_ptr(),
+                                            ctypes.c_void_p(stream))
     _check(rc)
     return M
 
