@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the matrix-free dense MTTKRP on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-configs]
+    python bench.py --schedules --dims 16384,2048,64 --rank 128 [--dtype f64] [--mode 2]
 
 One "step" is one pass of the whole hot path over the workload: one MTTKRP
 call per mode (k = 0..d-1) on the same resident tensor, i.e. d streaming
@@ -12,17 +13,29 @@ resident in HBM when the timed region starts.
 
 Prints ONE JSON line.  ``value`` is GB/s of X streamed over the whole step
 (d * N * s_f / t_step, wall clock between device synchronisations).
-``roofline`` is for the streaming kernel: algorithmic bytes per launch,
-s_f (N + R sum_n I_n) (the paper's infinite-cache model m_inf, Sec. IV-B),
-divided by the mean launch duration measured with HIP events recorded by the
-library on the launch stream around each streaming-kernel launch of the timed
-region.  ``cpu_baseline`` times the CPU oracle (long-double accumulation, as
-used for parity) on a bounded slab of the same tensor on the host cores.
+``roofline`` is for the main kernel of the calls (the streaming kernel, or the
+row-contraction kernel where the planner takes the second schedule):
+algorithmic bytes per launch, s_f (N + R sum_n I_n) (the paper's
+infinite-cache model m_inf, Sec. IV-B), or executed flops 2 N R where the
+rank makes the path compute-bound, divided by the mean launch duration
+measured with HIP events recorded by the library on the launch stream around
+each launch of the timed region.  ``configs`` repeats the measurement (its own
+warm-up and timed steps, same HIP-event timing) for every other benchmark
+configuration and for the paper's two tensor shapes, each with its own
+``roofline`` object and per-mode figures.  ``cpu_baseline`` times the CPU oracle
+(long-double accumulation, as used for parity) on a bounded slab of the same
+tensor on the host cores; ``cpu_baseline_native`` the same loop with the
+accumulator in the data type.
+
+``--schedules`` instead times one shape and mode (k != first) three ways, as the
+planner chooses, with the streaming kernel forced and with the second schedule
+(MFMA contraction over mode 0) forced, and prints a markdown table.
 """
 from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -33,9 +46,142 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published
 FP_PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3}   # dense MFMA = vector peak for these types
+DEFAULT_WORKLOAD = "c2_1024x1024x512_f64_R32"
+# measured next to the default workload when it is the one that is run
+OTHER_CONFIGS = (
+    "c1_64x64x64_f64_R16",
+    "c3_192x192x192x192_f64_R16",
+    "c4_48x48x48x48x48_f32_R64",
+    "c5_16384x2048x64_f64_R4",
+    "c5_16384x2048x64_f64_R8",
+    "c5_16384x2048x64_f64_R128",
+    "paperA_401x201x12x501_f64_R32",
+    "paperA_401x201x12x501_f64_R10",
+    "paperB_129x129x129x12x39_f64_R32",
+    "paperB_cp10_129x129x129x12x39_f64_R10",
+)
 
 
-def cpu_baseline(w, X, A, budget_s=15.0):
+def measured_traffic(workload: str):
+    """HBM bytes per main-kernel launch from the rocprofv3 counter runs summarised under
+    profiles/ (fetched + written, each scaled by what the same counter reads for a plain copy of
+    known size), or None when none was recorded for the workload."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "pmc_traffic.json")) as f:
+            return json.load(f).get(workload)
+    except (OSError, ValueError):
+        return None
+
+
+def roofline_of(w, kernel_ms, launches, perf_model):
+    """The roofline object of one workload from the mean duration of its main kernel."""
+    alg_bytes = perf_model.m_inf(w.dims, w.R, w.itemsize)   # per launch
+    exec_flops = 2.0 * w.numel * w.R
+    mem_bound = exec_flops / (FP_PEAK_TFLOPS[w.dtype] * 1e12) <= alg_bytes / (HBM_PEAK_GBPS * 1e9)
+    if mem_bound:
+        achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+        r = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+             "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4)}
+    else:
+        achieved = exec_flops / (kernel_ms * 1e-3) / 1e12
+        r = {"bound": "mfma", "achieved": round(achieved, 2),
+             "peak": FP_PEAK_TFLOPS[w.dtype], "unit": "TFLOP/s",
+             "frac": round(achieved / FP_PEAK_TFLOPS[w.dtype], 4)}
+    r["kernel"] = "mttkrp_stream_kernel (mttkrp_rowsum_kernel for modes on the second schedule)"
+    r["kernel_ms_mean"] = round(kernel_ms, 4)
+    r["launches_timed"] = launches
+    r["algorithmic_bytes_per_launch"] = alg_bytes
+    r["executed_flops_per_launch"] = exec_flops
+    detail = measured_traffic(w.name)
+    r["traffic"] = detail["total_bytes"] if detail else None
+    r["traffic_detail"] = detail
+    return r
+
+
+def run_workload(mt, perf_model, w, X, A, steps, warmup):
+    """W warm-up steps, then exactly K timed steps between two synchronisations, with the
+    library's HIP events around every kernel.  Returns (ms_per_step, per_mode, roofline)."""
+    import torch
+    M = [torch.empty((I, w.R), dtype=w.torch_dtype, device=X.device) for I in w.dims]
+
+    def step():
+        for k in range(w.ndim):
+            mt.mttkrp_dense(X, w.dims, A, k, M=M[k])
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    mt.mttkrp_timing_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    t_wall = time.perf_counter() - t0
+    mt.mttkrp_timing_enable(False)
+    ms_per_step = 1e3 * t_wall / steps
+
+    n_calls = mt.mttkrp_timing_count()
+    first = max(0, n_calls - 512)           # the library keeps the last 512 timed calls
+    first += (-first) % w.ndim              # start on a mode-1 call
+    s_ms = [[] for _ in range(w.ndim)]
+    c_ms = [[] for _ in range(w.ndim)]
+    for i in range(first, n_calls):
+        a, b = mt.mttkrp_timing_get(i)
+        s_ms[i % w.ndim].append(a)
+        c_ms[i % w.ndim].append(b)
+    per_mode = []
+    main_all = []
+    xb = w.numel * w.itemsize
+    mem_floor = perf_model.m_inf(w.dims, w.R, w.itemsize) / (HBM_PEAK_GBPS * 1e9) * 1e3
+    fp_floor = 2.0 * w.numel * w.R / (FP_PEAK_TFLOPS[w.dtype] * 1e12) * 1e3
+    for k in range(w.ndim):
+        main_all += s_ms[k]
+        sm = sum(s_ms[k]) / len(s_ms[k])
+        cm = sum(c_ms[k]) / len(c_ms[k])
+        plan = mt.mttkrp_plan_describe(w.dims, w.R, k, w.itemsize)
+        per_mode.append({
+            "mode": k + 1,
+            "main_kernel_ms": round(sm, 4),
+            "main_kernel_ms_min": round(min(s_ms[k]), 4),
+            "combine_kernel_ms": round(cm, 4),
+            "GBps_X": round(xb / (sm + cm) / 1e6, 1),
+            "pct_hbm": round(100 * xb / (sm + cm) / 1e6 / HBM_PEAK_GBPS, 1),
+            "gflops_exec_2NR": round(2 * w.numel * w.R / (sm + cm) / 1e6, 1),
+            "pct_fp_peak": round(100 * 2 * w.numel * w.R / (sm + cm) / 1e9 / FP_PEAK_TFLOPS[w.dtype], 1),
+            "gflops_paper_NRd": round(w.numel * w.R * w.ndim / (sm + cm) / 1e6, 1),
+            "roofline_frac": round(max(mem_floor, fp_floor) / sm, 4),
+            "schedule": "rows" if "shape=rows" in plan else "streaming",
+            "plan": plan,
+        })
+    kernel_ms = sum(main_all) / len(main_all)
+    return ms_per_step, per_mode, roofline_of(w, kernel_ms, len(main_all), perf_model)
+
+
+def config_entry(mt, perf_model, inputs, w, X, A):
+    """One element of ``configs``: warm up for about 0.15 s of load (the shader clock settles over
+    the first ~0.1 s), then time about 0.25 s worth of steps."""
+    import torch
+    for k in range(w.ndim):
+        mt.mttkrp_dense(X, w.dims, A, k)
+    torch.cuda.synchronize()                 # first calls also grow the workspace
+    t0 = time.perf_counter()
+    for k in range(w.ndim):
+        mt.mttkrp_dense(X, w.dims, A, k)
+    torch.cuda.synchronize()
+    t_step = max(time.perf_counter() - t0, 1e-5)
+    warmup = int(min(200, max(3, math.ceil(0.15 / t_step))))
+    steps = int(min(512 // w.ndim, max(5, math.ceil(0.25 / t_step))))
+    ms_per_step, per_mode, roofline = run_workload(mt, perf_model, w, X, A, steps, warmup)
+    xb = w.numel * w.itemsize
+    return {
+        "workload": w.name, "dims": list(w.dims), "R": w.R, "dtype": w.dtype, "x_bytes": xb,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4),
+        "value": round(w.ndim * xb / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
+        "per_mode": per_mode, "roofline": roofline,
+    }
+
+
+def cpu_baseline(w, X, A, budget_s, native):
     """Time the oracle on the slab X[..., :s] of the workload (all modes).
 
     The slab is the first s entries of the slowest mode, which is a contiguous
@@ -43,7 +189,6 @@ def cpu_baseline(w, X, A, budget_s=15.0):
     is linear in s.  s is chosen from a short calibration run so that the timed
     part takes about ``budget_s`` seconds.
     """
-    import numpy as np
     from oracle import mttkrp_oracle as orc
     from paper_2510_14891_amd import inputs
     orc.build()
@@ -57,7 +202,7 @@ def cpu_baseline(w, X, A, budget_s=15.0):
         As[-1] = As[-1][:s]
         t0 = time.perf_counter()
         for k in range(w.ndim):
-            orc.mttkrp(Xs, As, k)
+            orc.mttkrp(Xs, As, k, native_acc=native)
         return time.perf_counter() - t0
 
     s0 = max(1, min(w.dims[-1], (1 << 22) // max(lead, 1)))
@@ -66,16 +211,69 @@ def cpu_baseline(w, X, A, budget_s=15.0):
     t = run(s) if s > s0 else t_cal
     x_bytes = w.ndim * lead * s * w.itemsize
     return {
-        "value": x_bytes / t / 1e9,
+        "value": round(x_bytes / t / 1e9, 3),
         "unit": "GB/s of X streamed",
         "cores": cores,
         "kind": "oracle",
-        "accumulator": "long double",
+        "accumulator": ("the data type (%s)" % w.dtype) if native else "long double",
         "seconds": round(t, 3),
-        "gflops_paper": w.ndim * (lead * s) * w.R * w.ndim / t / 1e9,
+        "gflops_paper": round(w.ndim * (lead * s) * w.R * w.ndim / t / 1e9, 2),
         "sample": "slab X[..., :%d] of the last mode (%d of %d entries, %.1f %% of the tensor), "
                   "all %d modes, one run" % (s, lead * s, w.numel, 100.0 * s / w.dims[-1], w.ndim),
     }
+
+
+def compare_schedules(args) -> int:
+    """The library's two schedules side by side on one shape and mode (k != first)."""
+    import torch
+    from paper_2510_14891_amd import binding as mt
+    mt.lib()
+    dims = tuple(int(t) for t in args.dims.split(","))
+    k = args.mode - 1
+    if not 1 <= k < len(dims):
+        print("bench.py --schedules: --mode must be between 2 and the number of modes", file=sys.stderr)
+        return 2
+    R = args.rank
+    dt = torch.float64 if args.dtype == "f64" else torch.float32
+    sb = 8 if args.dtype == "f64" else 4
+    n = math.prod(dims)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1)
+    X = torch.rand(n, dtype=dt, device="cuda", generator=g)
+    A = [torch.rand((I, R), dtype=dt, device="cuda", generator=g) for I in dims]
+    M = torch.empty((dims[k], R), dtype=dt, device="cuda")
+    settings = (("planner", 0), ("streaming kernel", 2), ("second schedule", 1))
+    reps, ref, rows = 11, None, {}
+    try:
+        for _ in range(2):                   # the second pass is reported: none sits in the clock ramp
+            for name, val in settings:
+                mt.mttkrp_tune_set("contract_rows", val)
+                desc = mt.mttkrp_plan_describe(dims, R, k, sb)
+                for _ in range(3):
+                    mt.mttkrp_dense(X, dims, A, k, M=M)
+                torch.cuda.synchronize()
+                mt.mttkrp_timing_enable(True)
+                for _ in range(reps):
+                    mt.mttkrp_dense(X, dims, A, k, M=M)
+                torch.cuda.synchronize()
+                c = mt.mttkrp_timing_count()
+                ts = sorted(sum(mt.mttkrp_timing_get(i)) for i in range(c - reps, c))
+                mt.mttkrp_timing_enable(False)
+                if ref is None:
+                    ref = M.clone()
+                diff = float(torch.linalg.vector_norm(M - ref) / torch.linalg.vector_norm(ref))
+                rows[name] = (ts[reps // 2], desc, diff)
+    finally:
+        mt.mttkrp_tune_set("contract_rows", 0)
+    print("| shape | R | type | mode | setting | ms | GB/s of X | TFLOP/s | schedule | rel. difference |")
+    print("|---|---|---|---|---|---|---|---|---|---|")
+    for name, _ in settings:
+        ms, desc, diff = rows[name]
+        sched = "second (rows)" if "shape=rows" in desc else "streaming"
+        print("| %s | %d | %s | %d | %s | %.3f | %.0f | %.1f | %s | %.1e |" % (
+            "x".join(str(d) for d in dims), R, args.dtype, args.mode, name, ms, n * sb / ms / 1e6,
+            2.0 * n * R / ms / 1e9, sched, diff))
+    return 0
 
 
 def main() -> int:
@@ -84,12 +282,19 @@ def main() -> int:
     # defaults: the shader clock settles over the first ~0.1 s of sustained load, so warm up that long
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--workload", default="c2_1024x1024x512_f64_R32")
-    ap.add_argument("--cpu-budget", type=float, default=15.0,
-                    help="seconds of oracle time for the CPU baseline (0 = skip)")
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the `configs` array (the other configurations, measured after the main one)")
+    ap.add_argument("--cpu-budget", type=float, default=10.0,
+                    help="seconds of oracle time for each of the two CPU baselines (0 = skip)")
     ap.add_argument("--copy-only", action="store_true",
                     help="run only K plain device copies of the X buffer (the known-size "
                          "kernel the rocprofv3 FETCH_SIZE/WRITE_SIZE counters are scaled by)")
+    ap.add_argument("--schedules", action="store_true", help="compare the two schedules on --dims/--rank/--mode")
+    ap.add_argument("--dims", default="16384,2048,64")
+    ap.add_argument("--rank", type=int, default=128)
+    ap.add_argument("--dtype", default="f64", choices=["f64", "f32"])
+    ap.add_argument("--mode", type=int, default=2, help="1-based mode k for --schedules")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path is one GPU's share at its "
@@ -103,12 +308,13 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     mt.lib()   # fails loudly when the HIP library is missing
-    w = inputs.WORKLOADS[args.workload]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.schedules:
+        return compare_schedules(args)
+    w = inputs.WORKLOADS[args.workload]
     X = inputs.make_tensor(w, device=dev)
     A = inputs.make_factors(w, device=dev)
-    M = [torch.empty((I, w.R), dtype=w.torch_dtype, device=dev) for I in w.dims]
     torch.cuda.synchronize()
     if args.copy_only:
         Y = torch.empty_like(X)
@@ -119,76 +325,13 @@ def main() -> int:
                           "bytes_written_per_copy": w.numel * w.itemsize, "copies": args.steps}))
         return 0
 
-    def step():
-        for k in range(w.ndim):
-            mt.mttkrp_dense(X, w.dims, A, k, M=M[k])
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
     # timed region: exactly K steps, wall clock between synchronisations.  The
     # library records HIP events on the launch stream around every kernel of
     # these K steps; they are read back after the region has ended.
-    mt.mttkrp_timing_enable(True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t_wall = time.perf_counter() - t0
-    ms_per_step = 1e3 * t_wall / args.steps
-    mt.mttkrp_timing_enable(False)
-
-    n_calls = mt.mttkrp_timing_count()
-    first = max(0, n_calls - 512)           # the library keeps the last 512 timed calls
-    s_ms = [[] for _ in range(w.ndim)]
-    c_ms = [[] for _ in range(w.ndim)]
-    for i in range(first, n_calls):
-        a, b = mt.mttkrp_timing_get(i)
-        s_ms[i % w.ndim].append(a)
-        c_ms[i % w.ndim].append(b)
-    per_mode = []
-    stream_ms_all = []
-    for k in range(w.ndim):
-        stream_ms_all += s_ms[k]
-        sm = sum(s_ms[k]) / len(s_ms[k])
-        cm = sum(c_ms[k]) / len(c_ms[k])
-        per_mode.append({
-            "mode": k + 1,
-            "stream_kernel_ms": round(sm, 4),
-            "stream_kernel_ms_min": round(min(s_ms[k]), 4),
-            "combine_kernel_ms": round(cm, 4),
-            "GBps_X": round(w.numel * w.itemsize / (sm + cm) / 1e6, 1),
-            "pct_hbm": round(100 * w.numel * w.itemsize / (sm + cm) / 1e6 / HBM_PEAK_GBPS, 1),
-            "gflops_exec_2NR": round(2 * w.numel * w.R / (sm + cm) / 1e6, 1),
-            "pct_fp_peak": round(100 * 2 * w.numel * w.R / (sm + cm) / 1e9
-                                 / FP_PEAK_TFLOPS[w.dtype], 1),
-            "gflops_paper_NRd": round(w.numel * w.R * w.ndim / (sm + cm) / 1e6, 1),
-            "plan": mt.mttkrp_plan_describe(w.dims, w.R, k, w.itemsize),
-        })
-    kernel_ms = sum(stream_ms_all) / len(stream_ms_all)
-
-    alg_bytes = perf_model.m_inf(w.dims, w.R, w.itemsize)   # per launch
-    exec_flops = 2.0 * w.numel * w.R
-    mem_bound = exec_flops / (FP_PEAK_TFLOPS[w.dtype] * 1e12) <= alg_bytes / (HBM_PEAK_GBPS * 1e9)
-    if mem_bound:
-        achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4)}
-    else:
-        achieved = exec_flops / (kernel_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "achieved": round(achieved, 2),
-                    "peak": FP_PEAK_TFLOPS[w.dtype], "unit": "TFLOP/s",
-                    "frac": round(achieved / FP_PEAK_TFLOPS[w.dtype], 4)}
-    roofline["kernel"] = "mttkrp_stream_kernel"
-    roofline["kernel_ms_mean"] = round(kernel_ms, 4)
-    roofline["launches_timed"] = len(stream_ms_all)
-    roofline["algorithmic_bytes_per_launch"] = alg_bytes
-    # HBM bytes per launch from the rocprofv3 counter runs recorded under profiles/ (fetched + written,
-    # each scaled by what the same counter reads for a plain copy of known size), or null
-    detail = perf_model.measured_traffic(w.name)
-    roofline["traffic"] = detail["total_bytes"] if detail else None
-    roofline["traffic_detail"] = detail
+    ms_per_step, per_mode, roofline = run_workload(mt, perf_model, w, X, A, args.steps, args.warmup)
+    kernel_ms = roofline["kernel_ms_mean"]
+    alg_bytes = roofline["algorithmic_bytes_per_launch"]
+    exec_flops = roofline["executed_flops_per_launch"]
 
     x_gbps = w.ndim * w.numel * w.itemsize / (ms_per_step * 1e-3) / 1e9
     out = {
@@ -229,7 +372,30 @@ def main() -> int:
                "its clock drops further than the kernel's, so a ratio above 1 can occur",
     }
     if args.cpu_budget > 0:
-        out["cpu_baseline"] = cpu_baseline(w, X, A, args.cpu_budget)
+        out["cpu_baseline"] = cpu_baseline(w, X, A, args.cpu_budget, native=False)
+        out["cpu_baseline_native"] = cpu_baseline(w, X, A, args.cpu_budget, native=True)
+
+    # Every other configuration, each with its own warm-up, timed steps and roofline object
+    # (same HIP-event timing).  Tensors that share a recipe (configuration 5's three ranks)
+    # are generated once.
+    if not args.no_configs and args.workload == DEFAULT_WORKLOAD:
+        del X, A
+        torch.cuda.empty_cache()
+        configs = []
+        cache_key, Xc = None, None
+        for name in OTHER_CONFIGS:
+            wc = inputs.WORKLOADS[name]
+            key = (wc.dims, wc.dtype, wc.x_dist, wc.seed_id)
+            if key != cache_key:
+                Xc = None
+                torch.cuda.empty_cache()
+                Xc = inputs.make_tensor(wc, device=dev)
+                cache_key = key
+            Ac = inputs.make_factors(wc, device=dev)
+            configs.append(config_entry(mt, perf_model, inputs, wc, Xc, Ac))
+        out["configs"] = configs
+        out["roofline_frac_by_workload"] = dict(
+            [(w.name, roofline["frac"])] + [(c["workload"], c["roofline"]["frac"]) for c in configs])
     print(json.dumps(out), flush=True)
     return 0
 

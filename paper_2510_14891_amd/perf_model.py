@@ -13,12 +13,8 @@ factors the product of Eq. (elem); both counts are reported.
 """
 from __future__ import annotations
 
-import json
 import math
-import os
-from typing import Optional, Sequence
-
-_ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+from typing import Sequence
 
 
 def numel(dims: Sequence[int]) -> int:
@@ -58,14 +54,3 @@ def predicted_time(flops: float, bytes_: float, tau_f: float, tau_m: float) -> f
 
 def gflops_paper_units(flops: float, seconds: float) -> float:
     return flops / seconds / 1024.0 ** 3
-
-
-def measured_traffic(workload: str) -> Optional[dict]:
-    """HBM bytes per streaming-kernel launch from the committed rocprofv3 PMC
-    summary (profiles/pmc_traffic.json), or None when none was recorded."""
-    path = os.path.join(_ROOT, "profiles", "pmc_traffic.json")
-    try:
-        with open(path) as f:
-            return json.load(f).get(workload)
-    except (OSError, ValueError):
-        return None
