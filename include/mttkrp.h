@@ -19,7 +19,8 @@
  * adjacent modes are treated as one (two short column modes; modes 0 and 1 when
  * I_0 fits the 16-row MFMA blocks badly), the row-wise product of their two
  * factors, which is only formed while it stays below a constant size (8 MiB by
- * default; at most two such matrices per call), or, for k != 0 with at most
+ * default for two column modes, 32 MiB for modes 0 and 1; at most two such
+ * matrices per call), or, for k != 0 with at most
  * 1024 entries in the modes other than 0 and k, the product of those modes'
  * factor rows (at most 1024 x R values).
  *
@@ -252,6 +253,10 @@ int mttkrp_timing_last(float* stream_ms, float* combine_ms);
  *                   0 = chosen by the planner
  *   "deep"          1 = always the kernel build with the software-pipelined run,
  *                   2 = always the build with batches only, 0 = by item length
+ *   "linear"        1 = the column space is split into balanced ranges of steps that may
+ *                   begin and end inside a sweep, 2 = only whole sweeps and equal pieces
+ *                   of sweeps, 0 = chosen by the planner (ranges for the first mode when
+ *                   the other way leaves the work items uneven)
  * Returns MTTKRP_ERR_INVALID_ARG for an unknown key or a value out of range.
  */
 int mttkrp_tune_set(const char* key, int64_t value);

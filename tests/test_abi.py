@@ -84,7 +84,7 @@ def test_workspace_stays_in_the_sum_of_dims_class(mt):
             fused = int(re.search(r"fused_bytes=(\d+)", desc).group(1))
             part = slots * w.dims[k] * w.R * w.itemsize if slots > 1 else 0
             assert ws == (part + 255) // 256 * 256 + fused
-            assert fused <= 2 * (8 << 20)    # at most two product matrices of fused modes, each small
+            assert fused <= (8 << 20) + (32 << 20)    # at most two product matrices of fused modes (columns, rows), each small
             assert slots <= 4096, (name, k, slots)
 
 

@@ -31,7 +31,7 @@ def mt():
 
 
 TUNE_KEYS = ("row_blocks", "target_items", "max_steps", "xcd_remap", "ws_percent",
-             "max_col_blocks", "first_group", "deep", "waves_per_simd", "nt_loads", "fuse_bytes", "inner_splits", "contract_rows", "rows_col_blocks")
+             "max_col_blocks", "first_group", "deep", "waves_per_simd", "nt_loads", "fuse_bytes", "inner_splits", "contract_rows", "rows_col_blocks", "linear")
 
 
 def make_problem(dims, R, dtype, seed, dist=("uniform", -1.0, 1.0)):
@@ -239,6 +239,8 @@ def test_result_does_not_depend_on_the_decomposition(mt, oracle, dtype):
         {"contract_rows": 1}, {"contract_rows": 1, "max_steps": 3}, {"contract_rows": 1, "max_col_blocks": 1},
         {"contract_rows": 2},
         {"fuse_bytes": 1}, {"inner_splits": 1}, {"inner_splits": 5}, {"fuse_bytes": 1 << 30}, {"fuse_bytes": 1 << 30, "target_items": 64},
+        {"linear": 1}, {"linear": 1, "target_items": 777}, {"linear": 1, "first_group": 1, "target_items": 100000},
+        {"linear": 1, "deep": 2, "max_steps": 5}, {"linear": 2, "first_group": 1},
     ]
     try:
         for st in settings:
@@ -542,7 +544,8 @@ def test_seeded_random_shapes_long_first_mode(mt, oracle):
     Rs = (1, 3, 8, 16, 17, 32, 33, 49, 50, 64, 70, 100)
     tunes = ({}, {}, {"contract_rows": 1}, {"contract_rows": 1, "max_steps": 2}, {"contract_rows": 2},
              {"contract_rows": 1, "target_items": 100000}, {"fuse_bytes": 1 << 30}, {"target_items": 50000},
-             {"contract_rows": 1, "rows_col_blocks": 1}, {"inner_splits": 3}, {"max_steps": 3})
+             {"contract_rows": 1, "rows_col_blocks": 1}, {"inner_splits": 3}, {"max_steps": 3},
+             {"linear": 1}, {"linear": 1, "target_items": 30000}, {"linear": 1, "first_group": 1, "max_steps": 7})
     u = inputs.uniform(20240607, 150 * 16).numpy()
     try:
         for case in range(150):
