@@ -55,6 +55,9 @@
  *   MTTKRP_ERR_WORKSPACE    a *_ws call with too few workspace bytes, or
  *                           workspace not 256-byte aligned
  *   MTTKRP_ERR_DEVICE       a HIP runtime call failed
+ *   MTTKRP_ERR_NUMERICAL    (CP-ALS only) the input made a step of the iteration
+ *                           impossible: a Gram Hadamard product that is not
+ *                           positive definite
  */
 #ifndef MTTKRP_H
 #define MTTKRP_H
@@ -73,7 +76,8 @@ typedef enum {
     MTTKRP_ERR_INVALID_ARG = 1,
     MTTKRP_ERR_UNSUPPORTED = 2,
     MTTKRP_ERR_WORKSPACE = 3,
-    MTTKRP_ERR_DEVICE = 4
+    MTTKRP_ERR_DEVICE = 4,
+    MTTKRP_ERR_NUMERICAL = 5
 } mttkrp_status;
 
 /*

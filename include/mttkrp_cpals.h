@@ -62,9 +62,10 @@ int mttkrp_dense_all_modes_f32(int ndim, const int64_t* dims, const float* X,
  *   iters      host, written: sweeps done
  *   fits       host array of max_iters doubles (or NULL), fits[s] = fit after sweep s
  * Returns an mttkrp_status: MTTKRP_ERR_UNSUPPORTED for R above the limit,
- * MTTKRP_ERR_DEVICE when an allocation or a HIP call fails or when a Gram
- * Hadamard product is not positive definite (its Cholesky factor would hold a
- * non-positive pivot; the factors and lambda then hold the last completed update).
+ * MTTKRP_ERR_DEVICE when an allocation or a HIP call fails; MTTKRP_ERR_NUMERICAL
+ * when a Gram Hadamard product is not positive definite (its Cholesky factor would
+ * hold a non-positive pivot; the factors and lambda then hold the last completed
+ * update).
  */
 int mttkrp_cpals_f64(int ndim, const int64_t* dims, const double* X, double* const* factors,
                      double* lambda, int R, int max_iters, double tol, int* iters, double* fits,

@@ -20,6 +20,7 @@ MTTKRP_ERR_INVALID_ARG = 1
 MTTKRP_ERR_UNSUPPORTED = 2
 MTTKRP_ERR_WORKSPACE = 3
 MTTKRP_ERR_DEVICE = 4
+MTTKRP_ERR_NUMERICAL = 5
 MTTKRP_MAX_NDIM = 8
 
 # every symbol include/mttkrp.h declares

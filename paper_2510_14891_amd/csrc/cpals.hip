@@ -352,7 +352,7 @@ int mttkrp_cpals_f64(int ndim, const int64_t* dims, const double* X, double* con
             hipStreamSynchronize(st) != hipSuccess)
             return MTTKRP_ERR_DEVICE;
         if (flag)
-            return MTTKRP_ERR_DEVICE;   // a Gram Hadamard product was not positive definite
+            return MTTKRP_ERR_NUMERICAL;   // a Gram Hadamard product was not positive definite
         const double normX = sqrt(h[0]);
         double resid2 = h[0] + h[2] - 2.0 * h[1];
         if (resid2 < 0.0)

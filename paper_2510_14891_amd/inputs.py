@@ -183,6 +183,12 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     _wl("paperA_401x201x12x501_f64_R10", (401, 201, 12, 501), "f64", 10,
         ("uniform", 0.0, 1.0), ("uniform", 0.0, 1.0), 6,
         "shape of the paper's tearing-mode tensor, random values, the paper's smallest rank"),
+    _wl("paperA_401x201x12x501_f64_R1000", (401, 201, 12, 501), "f64", 1000,
+        ("uniform", 0.0, 1.0), ("uniform", 0.0, 1.0), 6,
+        "shape of the paper's tearing-mode tensor at one of its high ranks (Sec. IV-C, IV-D)"),
+    _wl("paperA_401x201x12x501_f64_R2000", (401, 201, 12, 501), "f64", 2000,
+        ("uniform", 0.0, 1.0), ("uniform", 0.0, 1.0), 6,
+        "shape of the paper's tearing-mode tensor at the paper's highest rank (Sec. IV-C, IV-D)"),
     _wl("paperB_129x129x129x12x39_f64_R32", (129, 129, 129, 12, 39), "f64", 32,
         ("uniform", 0.0, 1.0), ("uniform", 0.0, 1.0), 7,
         "shape of the paper's island-coalescence tensor, random values"),

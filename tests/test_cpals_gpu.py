@@ -125,6 +125,6 @@ def test_cpals_errors(mt):
     before = Ad[0].clone()
     with pytest.raises(mt.MttkrpError) as e:
         mt.mttkrp_cpals(Xd, dims, Ad, 2, 0.0)
-    assert e.value.status == mt.MTTKRP_ERR_DEVICE
+    assert e.value.status == mt.MTTKRP_ERR_NUMERICAL
     torch.cuda.synchronize()
     assert torch.equal(Ad[0], before)                           # the failed update left A_0 as it was

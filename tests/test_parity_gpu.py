@@ -577,3 +577,33 @@ def test_seeded_random_shapes_long_first_mode(mt, oracle):
     finally:
         for key in TUNE_KEYS:
             mt.mttkrp_tune_set(key, 0)
+
+
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+def test_non_finite_values_propagate_as_in_the_definition(mt, oracle, dtype):
+    """Plain IEEE propagation (the paper is silent on non-finite values): an infinite tensor
+    entry or factor entry makes exactly the sums of Eq. (elem) that contain it infinite.  The
+    entries sit in the last column of an inner mode whose extent is not a multiple of four (the
+    step that pads its lanes by re-reading that column) and in the last rows (re-read by the
+    shifted last row block); padding must not turn them into NaNs elsewhere."""
+    for dims, R in (((40, 7, 5), 6), ((70, 9, 3, 2), 20), ((33, 5), 3)):
+        X, A = make_problem(dims, R, dtype, seed=990, dist=("uniform", 0.1, 1.0))
+        Xv = inputs.as_ndarray_view(X, dims)
+        Xv[(dims[0] - 1, dims[1] - 1) + (0,) * (len(dims) - 2)] = np.inf
+        A[1][dims[1] - 1, R - 1] = np.inf
+        Xd, Ad = X.cuda(), [a.cuda() for a in A]
+        for k in range(len(dims)):
+            ref = oracle_mttkrp(oracle, X, dims, A, k)
+            for tune in ({}, {"deep": 2}, {"contract_rows": 1}, {"max_steps": 2}):
+                for key, val in tune.items():
+                    mt.mttkrp_tune_set(key, val)
+                got = mt.mttkrp_dense(Xd, dims, Ad, k).cpu().numpy()
+                for key in tune:
+                    mt.mttkrp_tune_set(key, 0)
+                assert not np.isnan(ref).any()
+                assert np.array_equal(np.isinf(got), np.isinf(ref)), (dims, k, tune)
+                assert not np.isnan(got).any(), (dims, k, tune)
+                fin = np.isfinite(ref)
+                assert fin.any()
+                err = oracle.normwise_rel_err(np.where(fin, got, 0.0), np.where(fin, ref, 0.0))
+                assert err <= TOL[dtype], (dims, k, tune, err)
