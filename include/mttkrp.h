@@ -171,6 +171,32 @@ int mttkrp_dense_f32_ld(int ndim, const int64_t* dims, const float* X,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Partial contraction over the leading index.  X is read as a P x Q matrix, first index
+ * fastest (for a d-way tensor: P = the product of the extents of modes 0 .. s-1, Q = the
+ * product of the others, no copy or permutation), and
+ *     T(c, j) = sum_{r = 0 .. P-1} X[r + P c] * K[r * ldK + j],    c < Q, j < R.
+ * With K the Khatri-Rao product of the factors of the leading modes (row r = the product of
+ * their rows at the multi-index of r, lowest mode fastest; for s = 1 the factor of mode 0
+ * itself) T is the part of the sum of Eq. (elem) that the modes s .. d-1 share: the mode-k
+ * MTTKRP is T weighted by the other trailing factors and summed over their indices.  For
+ * Q = I_{d-1} (s = d-1) T is the last mode's MTTKRP.
+ *   X, K, T_out  device pointers; T_out is Q x R row-major with leading dimension ldT >= R,
+ *                overwritten; K has leading dimension ldK >= R
+ *   workspace    device memory of mttkrp_contract_leading_workspace_bytes bytes (0 for most
+ *                shapes: partial sums are only needed when Q is too short to fill the chip
+ *                and P is split), may be NULL when that is 0
+ * Limits: P, Q < 2^31 - 64, R < 2^27.  Errors as for the core calls; the query returns
+ * (size_t)-1 for invalid or unsupported arguments.  Asynchronous on `stream`.
+ */
+size_t mttkrp_contract_leading_workspace_bytes(int64_t P, int64_t Q, int R, int dtype_bytes);
+int mttkrp_contract_leading_f64(int64_t P, int64_t Q, const double* X, const double* K, int64_t ldK,
+                                int R, double* T_out, int64_t ldT, void* workspace,
+                                size_t workspace_bytes, void* stream);
+int mttkrp_contract_leading_f32(int64_t P, int64_t Q, const float* X, const float* K, int64_t ldK,
+                                int R, float* T_out, int64_t ldT, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
+/*
  * mttkrp_dense_f64 for callers that cannot allocate device memory: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same operation, arguments, layouts and errors as mttkrp_dense_f64, and the

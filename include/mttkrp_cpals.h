@@ -52,6 +52,35 @@ int mttkrp_dense_all_modes_f32(int ndim, const int64_t* dims, const float* X,
                                void* stream);
 
 /*
+ * All-modes sweep that shares partial contractions between the modes: the same d results
+ * from two passes over X instead of d.  The modes are cut into a leading set 0 .. s-1
+ * (P_L = their extents' product) and a trailing set s .. d-1 (P_R); one pass contracts the
+ * trailing modes (an MTTKRP of X seen as a P_L x I_s x ... tensor, first mode), one the
+ * leading modes (mttkrp_contract_leading_* with the Khatri-Rao product of the leading
+ * factors); every mode's result then follows from one of the two intermediates (P_L x R and
+ * P_R x R values) by a small kernel.  The sums of Eq. (elem) are the same, taken in another
+ * order.  This trades memory for passes: the intermediates are in the class of the partial
+ * Khatri-Rao matrices of the paper's Table I, not in O(R sum I_n); the cut with the smallest
+ * intermediates is taken, and the call is only supported when everything fits an eighth of
+ * the tensor's bytes (or 64 MiB).
+ *   mttkrp_dense_all_modes_shared_bytes   bytes of `workspace` the call needs, 0 when the
+ *                                         shape is not supported (use mttkrp_dense_all_modes_*)
+ *   workspace   device memory, caller-owned, 256-byte aligned; contents need not be kept
+ *   other arguments as mttkrp_dense_all_modes_*; M_out[k] may be one buffer for all k only
+ *   if the caller consumes each result in stream order (the CP-ALS driver does).
+ * Returns MTTKRP_ERR_UNSUPPORTED for a shape without a cut that fits, MTTKRP_ERR_WORKSPACE
+ * for a workspace that is too small.  The core calls it makes use the library-owned
+ * workspace of the stream.
+ */
+size_t mttkrp_dense_all_modes_shared_bytes(int ndim, const int64_t* dims, int R, int dtype_bytes);
+int mttkrp_dense_all_modes_shared_f64(int ndim, const int64_t* dims, const double* X,
+                                      const double* const* factors, int R, double* const* M_out,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+int mttkrp_dense_all_modes_shared_f32(int ndim, const int64_t* dims, const float* X,
+                                      const float* const* factors, int R, float* const* M_out,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * CP-ALS in fp64.
  *   factors    host array of d device pointers; factors[m] is I_m x R: the
  *              initial guess on entry, the column-normalised factor on return
@@ -70,6 +99,18 @@ int mttkrp_dense_all_modes_f32(int ndim, const int64_t* dims, const float* X,
 int mttkrp_cpals_f64(int ndim, const int64_t* dims, const double* X, double* const* factors,
                      double* lambda, int R, int max_iters, double tol, int* iters, double* fits,
                      void* stream);
+
+/*
+ * The same iteration with every sweep done as in mttkrp_dense_all_modes_shared_f64 (factor k
+ * is updated right after its MTTKRP, so later modes see it exactly as in the plain driver;
+ * the intermediate of the trailing modes is formed before the leading factors change and
+ * does not contain them).  The driver allocates the intermediates' buffer itself; for a
+ * shape without a supported cut it runs the plain sweeps.  Results agree with
+ * mttkrp_cpals_f64 to rounding (the sums are taken in another order).
+ */
+int mttkrp_cpals_shared_f64(int ndim, const int64_t* dims, const double* X, double* const* factors,
+                            double* lambda, int R, int max_iters, double tol, int* iters,
+                            double* fits, void* stream);
 
 #ifdef __cplusplus
 }

@@ -35,6 +35,9 @@ EXPORTED = (
     "mttkrp_dense_all_modes_f64", "mttkrp_dense_all_modes_f32", "mttkrp_cpals_f64",
     "mttkrp_calibrate_stream", "mttkrp_calibrate_mfma",
     "mttkrp_dense_f64_ld", "mttkrp_dense_f32_ld", "mttkrp_dense_f64_noalloc",
+    "mttkrp_contract_leading_workspace_bytes", "mttkrp_contract_leading_f64", "mttkrp_contract_leading_f32",
+    "mttkrp_dense_all_modes_shared_bytes", "mttkrp_dense_all_modes_shared_f64",
+    "mttkrp_dense_all_modes_shared_f32", "mttkrp_cpals_shared_f64",
 )
 
 MTTKRP_SCHEDULE_ELEM = 1
@@ -113,10 +116,24 @@ def lib() -> ctypes.CDLL:
         getattr(L, name).restype = ctypes.c_int
         getattr(L, name).argtypes = [ctypes.c_int, i64p, ctypes.c_void_p, vpp, ctypes.c_int, vpp,
                                      ctypes.c_void_p]
-    L.mttkrp_cpals_f64.restype = ctypes.c_int
-    L.mttkrp_cpals_f64.argtypes = [ctypes.c_int, i64p, ctypes.c_void_p, vpp, ctypes.c_void_p, ctypes.c_int,
-                                   ctypes.c_int, ctypes.c_double, ctypes.POINTER(ctypes.c_int),
-                                   ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    for name in ("mttkrp_cpals_f64", "mttkrp_cpals_shared_f64"):
+        getattr(L, name).restype = ctypes.c_int
+        getattr(L, name).argtypes = [ctypes.c_int, i64p, ctypes.c_void_p, vpp, ctypes.c_void_p, ctypes.c_int,
+                                     ctypes.c_int, ctypes.c_double, ctypes.POINTER(ctypes.c_int),
+                                     ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    for name in ("mttkrp_dense_all_modes_shared_f64", "mttkrp_dense_all_modes_shared_f32"):
+        getattr(L, name).restype = ctypes.c_int
+        getattr(L, name).argtypes = [ctypes.c_int, i64p, ctypes.c_void_p, vpp, ctypes.c_int, vpp,
+                                     ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.mttkrp_dense_all_modes_shared_bytes.restype = ctypes.c_size_t
+    L.mttkrp_dense_all_modes_shared_bytes.argtypes = [ctypes.c_int, i64p, ctypes.c_int, ctypes.c_int]
+    L.mttkrp_contract_leading_workspace_bytes.restype = ctypes.c_size_t
+    L.mttkrp_contract_leading_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int]
+    for name in ("mttkrp_contract_leading_f64", "mttkrp_contract_leading_f32"):
+        getattr(L, name).restype = ctypes.c_int
+        getattr(L, name).argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                     ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_int64,
+                                     ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     ldargs = [ctypes.c_int, i64p, ctypes.c_void_p, vpp, i64p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     L.mttkrp_dense_f64_ld.restype = ctypes.c_int
     L.mttkrp_dense_f64_ld.argtypes = ldargs + [ctypes.c_double, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
@@ -369,9 +386,94 @@ def mttkrp_dense_all_modes(X, dims: Sequence[int], factors: Sequence, M_out=None
     return list(M_out)
 
 
+_scratch_buffers = {}
+
+
+def _scratch(device, stream, nbytes):
+    """A caller-owned workspace for the calls that take one: kept per (device, stream) and
+    grown on demand, so that it outlives the kernels that use it."""
+    import torch
+    key = (str(device), int(stream))
+    buf = _scratch_buffers.get(key)
+    if buf is None or buf.numel() < nbytes:
+        if buf is not None:
+            torch.cuda.synchronize(device)
+        buf = torch.empty(int(nbytes), dtype=torch.uint8, device=device)
+        _scratch_buffers[key] = buf
+    return buf
+
+
+def mttkrp_dense_all_modes_shared_bytes(dims: Sequence[int], R: int, dtype_bytes: int) -> int:
+    """Bytes of workspace the shared sweep needs; 0 when the shape has no supported cut."""
+    return int(lib().mttkrp_dense_all_modes_shared_bytes(len(dims), _dims_array(dims), int(R), int(dtype_bytes)))
+
+
+def mttkrp_dense_all_modes_shared(X, dims: Sequence[int], factors: Sequence, M_out=None,
+                                  stream: Optional[int] = None):
+    """[M_0, ..., M_{d-1}] from two passes over X (partial contractions shared between the
+    modes); see mttkrp_dense_all_modes_shared_f64 in include/mttkrp_cpals.h."""
+    import torch
+    L = lib()
+    suffix, d, ptrs, R, M0, stream = _marshal(X, dims, factors, 0, None if M_out is None else M_out[0], stream)
+    if any(f is None for f in factors):
+        raise ValueError("every factor is read by the all-modes sweep")
+    if M_out is None:
+        M_out = [M0] + [torch.empty((int(dims[k]), R), dtype=X.dtype, device=X.device) for k in range(1, d)]
+    outs = (ctypes.c_void_p * d)()
+    for k in range(d):
+        M = M_out[k]
+        if (M.dtype != X.dtype or M.device != X.device or not M.is_contiguous()
+                or tuple(M.shape) != (int(dims[k]), R)):
+            raise ValueError("M_out[%d] must be a contiguous (I_k, R) tensor like X" % k)
+        outs[k] = M.data_ptr()
+    nbytes = mttkrp_dense_all_modes_shared_bytes(dims, R, X.element_size())
+    if nbytes == 0:
+        raise MttkrpError(MTTKRP_ERR_UNSUPPORTED, "no supported cut for this shape")
+    ws = _scratch(X.device, stream, nbytes)
+    with torch.cuda.device(X.device):
+        rc = getattr(L, "mttkrp_dense_all_modes_shared_" + suffix)(
+            d, _dims_array(dims), X.data_ptr(), ptrs, R, outs, ws.data_ptr(), nbytes, ctypes.c_void_p(stream))
+    _check(rc)
+    return list(M_out)
+
+
+def mttkrp_contract_leading(X, P: int, Q: int, K, T_out=None, stream: Optional[int] = None):
+    """T (Q x R) = X^T K for X read as a P x Q matrix, first index fastest, and K (P x R);
+    see mttkrp_contract_leading_f64 in include/mttkrp.h."""
+    import torch
+    L = lib()
+    if X.dtype not in (torch.float64, torch.float32) or not X.is_cuda or not X.is_contiguous():
+        raise ValueError("X must be a contiguous float64/float32 tensor on the GPU")
+    if X.numel() != int(P) * int(Q):
+        raise ValueError("X must hold P * Q values")
+    if (K.dtype != X.dtype or K.device != X.device or K.dim() != 2 or K.shape[0] != int(P)
+            or K.stride(1) != 1):
+        raise ValueError("K must be a (P, R) tensor like X with unit column stride")
+    R = int(K.shape[1])
+    if T_out is None:
+        T_out = torch.empty((int(Q), R), dtype=X.dtype, device=X.device)
+    if (T_out.dtype != X.dtype or T_out.device != X.device or tuple(T_out.shape) != (int(Q), R)
+            or T_out.stride(1) != 1):
+        raise ValueError("T_out must be a (Q, R) tensor like X with unit column stride")
+    suffix = "f64" if X.dtype == torch.float64 else "f32"
+    if stream is None:
+        stream = torch.cuda.current_stream(X.device).cuda_stream
+    nbytes = int(L.mttkrp_contract_leading_workspace_bytes(int(P), int(Q), R, X.element_size()))
+    if nbytes == ctypes.c_size_t(-1).value:
+        raise MttkrpError(MTTKRP_ERR_UNSUPPORTED, "unsupported shape")
+    ws = _scratch(X.device, stream, max(nbytes, 1))
+    with torch.cuda.device(X.device):
+        rc = getattr(L, "mttkrp_contract_leading_" + suffix)(
+            int(P), int(Q), X.data_ptr(), K.data_ptr(), int(K.stride(0)), R, T_out.data_ptr(),
+            int(T_out.stride(0)), ws.data_ptr() if nbytes else None, nbytes, ctypes.c_void_p(stream))
+    _check(rc)
+    return T_out
+
+
 def mttkrp_cpals(X, dims: Sequence[int], factors: Sequence, max_iters: int, tol: float,
-                 stream: Optional[int] = None):
+                 stream: Optional[int] = None, shared: bool = False):
     """CP-ALS in fp64 on the GPU.  ``factors`` (initial guess) are updated in place.
+    ``shared``: sweeps share partial contractions between the modes (two passes over X).
     Returns (lambda tensor, list of fits per sweep)."""
     import torch
     L = lib()
@@ -384,8 +486,9 @@ def mttkrp_cpals(X, dims: Sequence[int], factors: Sequence, max_iters: int, tol:
     iters = ctypes.c_int(0)
     fits = (ctypes.c_double * int(max_iters))()
     with torch.cuda.device(X.device):
-        rc = L.mttkrp_cpals_f64(d, _dims_array(dims), X.data_ptr(), ptrs, lam.data_ptr(), R, int(max_iters),
-                                float(tol), ctypes.byref(iters), fits, ctypes.c_void_p(stream))
+        fn = L.mttkrp_cpals_shared_f64 if shared else L.mttkrp_cpals_f64
+        rc = fn(d, _dims_array(dims), X.data_ptr(), ptrs, lam.data_ptr(), R, int(max_iters),
+                float(tol), ctypes.byref(iters), fits, ctypes.c_void_p(stream))
     _check(rc)
     return lam, [float(fits[i]) for i in range(iters.value)]
 

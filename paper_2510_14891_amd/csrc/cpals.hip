@@ -236,8 +236,10 @@ struct Buffers {
     double* partial = nullptr;  // kNormBlocks + R values
     double* scalars = nullptr;  // ||X||^2, <X, X^>, ||X^||^2
     int* flag = nullptr;
+    void* shared_ws = nullptr;  // intermediates of the sweeps that share partial contractions
     ~Buffers()
     {
+        (void)hipFree(shared_ws);
         (void)hipFree(M); (void)hipFree(G); (void)hipFree(V); (void)hipFree(gram_ws);
         (void)hipFree(partial); (void)hipFree(scalars); (void)hipFree(flag);
     }
@@ -248,6 +250,333 @@ void gram(const double* A, int64_t I, int R, double* ws, double* G, hipStream_t 
     const int n_chunks = (int)ceil_div(I, kChunkRows);
     hipLaunchKernelGGL(gram_partial, dim3(n_chunks), dim3(256), (size_t)kChunkRows * R * sizeof(double), st, A, I, R, ws);
     hipLaunchKernelGGL(gram_reduce, dim3((unsigned)ceil_div(R * R, 256)), dim3(256), 0, st, ws, n_chunks, R * R, G);
+}
+
+
+// ---------------------------------------------------------------------------
+// Sweep that shares partial contractions between the modes (two passes over X).
+// ---------------------------------------------------------------------------
+
+// K(r, j) = prod over the modes m of A_m(r_m, j), r decomposed with the lowest mode fastest;
+// row-major with leading dimension R.  One thread per entry.
+template <typename T> struct ModeSet {
+    const T* A[MTTKRP_MAX_NDIM];
+    int64_t ld[MTTKRP_MAX_NDIM];
+    int32_t dim[MTTKRP_MAX_NDIM];
+    int32_t n;
+};
+template <typename T>
+__global__ void __launch_bounds__(256) khatri_rao_rows(const ModeSet<T> p, int64_t n_entries, int R, T* __restrict__ K)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n_entries)
+        return;
+    int64_t r = e / R;
+    const int j = (int)(e - r * R);
+    T v = (T)1;
+    for (int m = 0; m < p.n; ++m) {
+        const int64_t rn = r / p.dim[m];
+        v *= p.A[m][(r - rn * p.dim[m]) * p.ld[m] + j];
+        r = rn;
+    }
+    K[e] = v;
+}
+
+// One mode's MTTKRP from a partial contraction.  Tp (P x R, row-major, leading dimension R)
+// holds, for every multi-index i of the modes in `p` (lowest fastest, P entries) and every
+// column j, the sum of Eq. (elem) over the modes that are not in `p`, without the factors of
+// the modes in `p`.  Mode t of the set then gets
+//     M(i_t, j) = sum over the other indices of Tp(i, j) * prod_{m in p, m != t} A_m(i_m, j).
+// A workgroup owns (i_t, a segment of the other indices, TJ columns): thread (tj, to) adds
+// the entries o = to, to + TO, ... of its segment in fp64, the TO subtotals are added in
+// order, and the segment totals go to part[i_t][segment][R] for sum_segments.
+template <typename T, int TJ>
+__global__ void __launch_bounds__(256)
+partial_mode_kernel(const ModeSet<T> p, const T* __restrict__ Tp, int t, int R, int64_t n_others,
+                    int64_t others_per_seg, int n_seg, double* __restrict__ part)
+{
+    constexpr int TO = 256 / TJ;
+    __shared__ double red[TO][TJ + 1];
+    const int tj = threadIdx.x % TJ, to = threadIdx.x / TJ;
+    const int64_t it = blockIdx.x;
+    const int seg = blockIdx.y;
+    const int j = blockIdx.z * TJ + tj;
+    const int jj = j < R ? j : R - 1;
+    const int64_t o_begin = (int64_t)seg * others_per_seg;
+    const int64_t o_end = o_begin + others_per_seg < n_others ? o_begin + others_per_seg : n_others;
+    double acc = 0.0;
+    for (int64_t o = o_begin + to; o < o_end; o += TO) {
+        int64_t rem = o, row = 0, stride = 1;
+        double w = 1.0;
+        for (int m = 0; m < p.n; ++m) {
+            if (m == t) {
+                row += it * stride;
+            } else {
+                const int64_t q = rem / p.dim[m];
+                const int64_t im = rem - q * p.dim[m];
+                rem = q;
+                row += im * stride;
+                w *= (double)p.A[m][im * p.ld[m] + jj];
+            }
+            stride *= p.dim[m];
+        }
+        acc += (double)Tp[row * R + jj] * w;
+    }
+    red[to][tj] = acc;
+    __syncthreads();
+    if (to == 0 && j < R) {
+        double v = 0.0;
+        for (int q = 0; q < TO; ++q)
+            v += red[q][tj];
+        part[(it * n_seg + seg) * R + j] = v;
+    }
+}
+
+// M(i, j) = sum over the segments, in order.  One thread per entry.
+template <typename T>
+__global__ void __launch_bounds__(256)
+sum_segments(const double* __restrict__ part, int64_t n_entries, int R, int n_seg, T* __restrict__ M, int64_t ldM)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n_entries)
+        return;
+    const int64_t i = e / R;
+    const int j = (int)(e - i * R);
+    double v = 0.0;
+    for (int q = 0; q < n_seg; ++q)
+        v += part[(i * n_seg + q) * R + j];
+    M[i * ldM + j] = (T)v;
+}
+
+template <typename T> struct Calls;
+template <> struct Calls<double> {
+    static int dense(int nd, const int64_t* d, const double* X, const double* const* f, int R, int k, double* M, void* st)
+    { return mttkrp_dense_f64(nd, d, X, f, R, k, M, st); }
+    static int leading(int64_t P, int64_t Q, const double* X, const double* K, int R, double* out, void* ws, size_t wsb, void* st)
+    { return mttkrp_contract_leading_f64(P, Q, X, K, R, R, out, R, ws, wsb, st); }
+};
+template <> struct Calls<float> {
+    static int dense(int nd, const int64_t* d, const float* X, const float* const* f, int R, int k, float* M, void* st)
+    { return mttkrp_dense_f32(nd, d, X, f, R, k, M, st); }
+    static int leading(int64_t P, int64_t Q, const float* X, const float* K, int R, float* out, void* ws, size_t wsb, void* st)
+    { return mttkrp_contract_leading_f32(P, Q, X, K, R, R, out, R, ws, wsb, st); }
+};
+
+// Where the modes are cut into a leading set (modes 0 .. s-1, P_L entries) and a trailing
+// set (modes s .. d-1, P_R entries), and what lies where in the caller's buffer.
+struct SharedPlan {
+    int s = 0;
+    int64_t PL = 1, PR = 1;
+    int max_seg = 1;
+    size_t off_TR = 0, off_KL = 0, off_TL = 0, off_part = 0, off_lead = 0, lead_bytes = 0, total = 0;
+};
+
+size_t align256(size_t n) { return (n + 255) / 256 * 256; }
+
+// segments of the other indices for one mode: enough workgroups to fill the chip
+int segments(int64_t I_t, int64_t n_others)
+{
+    int64_t n = ceil_div(4096, I_t);
+    const int64_t most = ceil_div(n_others, 64);
+    if (n > most)
+        n = most;
+    return (int)(n < 1 ? 1 : n);
+}
+
+int plan_shared(int ndim, const int64_t* dims, int R, int sbytes, SharedPlan& sp)
+{
+    if (!dims || ndim < 2 || R < 1 || (sbytes != 4 && sbytes != 8))
+        return MTTKRP_ERR_INVALID_ARG;
+    if (ndim > MTTKRP_MAX_NDIM)
+        return MTTKRP_ERR_UNSUPPORTED;
+    int64_t N = 1;
+    for (int m = 0; m < ndim; ++m) {
+        if (dims[m] < 1)
+            return MTTKRP_ERR_INVALID_ARG;
+        if (N > ((int64_t)1 << 57) / dims[m])
+            return MTTKRP_ERR_INVALID_ARG;
+        N *= dims[m];
+    }
+    // the cut with the smallest intermediates
+    int best = 0;
+    int64_t best_sum = 0, PL = 1;
+    for (int s = 1; s < ndim; ++s) {
+        PL *= dims[s - 1];
+        const int64_t PR = N / PL;
+        if (PL >= ((int64_t)1 << 31) - 64 || PR >= ((int64_t)1 << 31) - 64)
+            continue;
+        if (best == 0 || PL + PR < best_sum) {
+            best = s;
+            best_sum = PL + PR;
+        }
+    }
+    if (best == 0)
+        return MTTKRP_ERR_UNSUPPORTED;
+    sp.s = best;
+    sp.PL = 1;
+    for (int m = 0; m < best; ++m)
+        sp.PL *= dims[m];
+    sp.PR = N / sp.PL;
+    const size_t row = (size_t)R * (size_t)sbytes;
+    size_t off = 0;
+    if (sp.s > 1) {
+        sp.off_TR = off;  off += align256((size_t)sp.PL * row);
+        sp.off_KL = off;  off += align256((size_t)sp.PL * row);
+    }
+    if (ndim - sp.s > 1) {
+        sp.off_TL = off;  off += align256((size_t)sp.PR * row);
+    }
+    // segment totals of partial_mode_kernel (fp64), the largest over the modes that use it
+    size_t part = 0;
+    sp.max_seg = 1;
+    for (int k = 0; k < ndim; ++k) {
+        const bool left = k < sp.s;
+        if ((left && sp.s == 1) || (!left && ndim - sp.s == 1))
+            continue;
+        const int n_seg = segments(dims[k], (left ? sp.PL : sp.PR) / dims[k]);
+        const size_t b = (size_t)dims[k] * (size_t)n_seg * (size_t)R * sizeof(double);
+        if (b > part)
+            part = b;
+        if (n_seg > sp.max_seg)
+            sp.max_seg = n_seg;
+    }
+    sp.off_part = off;  off += align256(part);
+    const size_t lead = mttkrp_contract_leading_workspace_bytes(sp.PL, sp.PR, R, sbytes);
+    if (lead == (size_t)-1)
+        return MTTKRP_ERR_UNSUPPORTED;
+    sp.lead_bytes = lead;
+    sp.off_lead = off;  off += align256(lead);
+    sp.total = off > 0 ? off : 256;
+    // the intermediates must stay small beside the tensor: an eighth of it, or 64 MiB
+    double limit = 0.125 * (double)N * sbytes;
+    if (limit < 64.0 * 1048576.0)
+        limit = 64.0 * 1048576.0;
+    if ((double)sp.total > limit)
+        return MTTKRP_ERR_UNSUPPORTED;
+    return MTTKRP_OK;
+}
+
+template <typename T>
+int mode_from_partial(const T* Tp, int n, const int64_t* dims, const T* const* factors, int t, int R, T* M,
+                      double* part, hipStream_t st)
+{
+    ModeSet<T> ms;
+    ms.n = n;
+    int64_t P = 1;
+    for (int m = 0; m < n; ++m) {
+        ms.A[m] = m == t ? nullptr : factors[m];
+        ms.ld[m] = R;
+        ms.dim[m] = (int32_t)dims[m];
+        P *= dims[m];
+    }
+    const int64_t n_others = P / dims[t];
+    const int n_seg = segments(dims[t], n_others);
+    const int64_t per_seg = ceil_div(n_others, n_seg);
+    if (dims[t] >= ((int64_t)1 << 31) || n_seg > 65535)
+        return MTTKRP_ERR_UNSUPPORTED;
+    if (R >= 32) {
+        const int64_t jt = ceil_div(R, 32);
+        if (jt > 65535)
+            return MTTKRP_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL((partial_mode_kernel<T, 32>), dim3((unsigned)dims[t], (unsigned)n_seg, (unsigned)jt), dim3(256), 0, st,
+                           ms, Tp, t, R, n_others, per_seg, n_seg, part);
+    } else if (R > 8) {
+        hipLaunchKernelGGL((partial_mode_kernel<T, 16>), dim3((unsigned)dims[t], (unsigned)n_seg, (unsigned)ceil_div(R, 16)), dim3(256), 0, st,
+                           ms, Tp, t, R, n_others, per_seg, n_seg, part);
+    } else {
+        hipLaunchKernelGGL((partial_mode_kernel<T, 8>), dim3((unsigned)dims[t], (unsigned)n_seg, 1), dim3(256), 0, st,
+                           ms, Tp, t, R, n_others, per_seg, n_seg, part);
+    }
+    const int64_t n_entries = dims[t] * (int64_t)R;
+    hipLaunchKernelGGL((sum_segments<T>), dim3((unsigned)ceil_div(n_entries, 256)), dim3(256), 0, st,
+                       part, n_entries, R, n_seg, M, (int64_t)R);
+    return hipGetLastError() == hipSuccess ? MTTKRP_OK : MTTKRP_ERR_DEVICE;
+}
+
+// The sweep: M_out[k] for k = 0 .. d-1 in this order; after(k) runs right after M_out[k] has
+// been enqueued (CP-ALS updates factors[k] there: later modes then read the new factor, as in
+// d separate calls).  Two passes over X: one contracts the trailing modes (every leading
+// mode's result follows from it), one the leading modes.
+template <typename T, typename After>
+int shared_sweep(int ndim, const int64_t* dims, const T* X, const T* const* factors, int R, T* const* M_out,
+                 void* workspace, size_t workspace_bytes, void* stream, After after)
+{
+    if (!X || !factors || !M_out)
+        return MTTKRP_ERR_INVALID_ARG;
+    SharedPlan sp;
+    int rc = plan_shared(ndim, dims, R, (int)sizeof(T), sp);
+    if (rc != MTTKRP_OK)
+        return rc;
+    if (!workspace || workspace_bytes < sp.total)
+        return MTTKRP_ERR_WORKSPACE;
+    for (int m = 0; m < ndim; ++m)
+        if (!factors[m] || !M_out[m])
+            return MTTKRP_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    char* const ws = (char*)workspace;
+    double* const part = (double*)(ws + sp.off_part);
+    const int s = sp.s, nr = ndim - s;
+    // pass 1: contraction over the trailing modes
+    if (s == 1) {
+        rc = Calls<T>::dense(ndim, dims, X, factors, R, 0, M_out[0], stream);
+        if (rc != MTTKRP_OK)
+            return rc;
+        rc = after(0);
+        if (rc != MTTKRP_OK)
+            return rc;
+    } else {
+        int64_t d2[MTTKRP_MAX_NDIM];
+        const T* f2[MTTKRP_MAX_NDIM];
+        d2[0] = sp.PL;
+        f2[0] = nullptr;
+        for (int m = 0; m < nr; ++m) {
+            d2[1 + m] = dims[s + m];
+            f2[1 + m] = factors[s + m];
+        }
+        T* const TR = (T*)(ws + sp.off_TR);
+        rc = Calls<T>::dense(1 + nr, d2, X, f2, R, 0, TR, stream);
+        if (rc != MTTKRP_OK)
+            return rc;
+        for (int k = 0; k < s; ++k) {
+            rc = mode_from_partial<T>(TR, s, dims, factors, k, R, M_out[k], part, st);
+            if (rc != MTTKRP_OK)
+                return rc;
+            rc = after(k);
+            if (rc != MTTKRP_OK)
+                return rc;
+        }
+    }
+    // pass 2: contraction over the leading modes, whose factors are final now
+    const T* K = factors[0];
+    if (s > 1) {
+        ModeSet<T> ms;
+        ms.n = s;
+        for (int m = 0; m < s; ++m) {
+            ms.A[m] = factors[m];
+            ms.ld[m] = R;
+            ms.dim[m] = (int32_t)dims[m];
+        }
+        T* const KL = (T*)(ws + sp.off_KL);
+        const int64_t n_entries = sp.PL * (int64_t)R;
+        hipLaunchKernelGGL((khatri_rao_rows<T>), dim3((unsigned)ceil_div(n_entries, 256)), dim3(256), 0, st,
+                           ms, n_entries, R, KL);
+        K = KL;
+    }
+    T* const TL = nr == 1 ? M_out[ndim - 1] : (T*)(ws + sp.off_TL);
+    rc = Calls<T>::leading(sp.PL, sp.PR, X, K, R, TL, ws + sp.off_lead, sp.lead_bytes, stream);
+    if (rc != MTTKRP_OK)
+        return rc;
+    if (nr == 1)
+        return after(ndim - 1);
+    for (int k = s; k < ndim; ++k) {
+        rc = mode_from_partial<T>(TL, nr, dims + s, factors + s, k - s, R, M_out[k], part, st);
+        if (rc != MTTKRP_OK)
+            return rc;
+        rc = after(k);
+        if (rc != MTTKRP_OK)
+            return rc;
+    }
+    return MTTKRP_OK;
 }
 
 }  // namespace
@@ -280,8 +609,36 @@ int mttkrp_dense_all_modes_f32(int ndim, const int64_t* dims, const float* X, co
     return MTTKRP_OK;
 }
 
-int mttkrp_cpals_f64(int ndim, const int64_t* dims, const double* X, double* const* factors, double* lambda,
-                     int R, int max_iters, double tol, int* iters, double* fits, void* stream)
+size_t mttkrp_dense_all_modes_shared_bytes(int ndim, const int64_t* dims, int R, int dtype_bytes)
+{
+    SharedPlan sp;
+    if (plan_shared(ndim, dims, R, dtype_bytes, sp) != MTTKRP_OK)
+        return 0;
+    return sp.total;
+}
+
+int mttkrp_dense_all_modes_shared_f64(int ndim, const int64_t* dims, const double* X, const double* const* factors,
+                                      int R, double* const* M_out, void* workspace, size_t workspace_bytes,
+                                      void* stream)
+{
+    return shared_sweep<double>(ndim, dims, X, factors, R, M_out, workspace, workspace_bytes, stream,
+                                [](int) { return (int)MTTKRP_OK; });
+}
+
+int mttkrp_dense_all_modes_shared_f32(int ndim, const int64_t* dims, const float* X, const float* const* factors,
+                                      int R, float* const* M_out, void* workspace, size_t workspace_bytes,
+                                      void* stream)
+{
+    return shared_sweep<float>(ndim, dims, X, factors, R, M_out, workspace, workspace_bytes, stream,
+                               [](int) { return (int)MTTKRP_OK; });
+}
+
+}  // extern "C"
+
+namespace {
+
+int cpals_run(int ndim, const int64_t* dims, const double* X, double* const* factors, double* lambda,
+              int R, int max_iters, double tol, int* iters, double* fits, void* stream, bool shared)
 {
     if (!dims || !X || !factors || !lambda || !iters || ndim < 2 || R < 1 || max_iters < 1 || !(tol >= 0.0))
         return MTTKRP_ERR_INVALID_ARG;
@@ -303,6 +660,12 @@ int mttkrp_cpals_f64(int ndim, const int64_t* dims, const double* X, double* con
     hipStream_t st = (hipStream_t)stream;
     const int RR = R * R;
     Buffers b;
+    // shared sweeps: the intermediates' buffer; without a cut that fits, d separate passes
+    SharedPlan sp;
+    if (shared && plan_shared(ndim, dims, R, (int)sizeof(double), sp) != MTTKRP_OK)
+        shared = false;
+    if (shared && hipMalloc(&b.shared_ws, sp.total) != hipSuccess)
+        return MTTKRP_ERR_DEVICE;
     const int64_t max_chunks = ceil_div(max_I, kChunkRows);
     if (hipMalloc(&b.M, (size_t)max_I * R * sizeof(double)) != hipSuccess ||
         hipMalloc(&b.G, (size_t)ndim * RR * sizeof(double)) != hipSuccess ||
@@ -324,20 +687,34 @@ int mttkrp_cpals_f64(int ndim, const int64_t* dims, const double* X, double* con
         return MTTKRP_ERR_DEVICE;
 
     const double* cf[MTTKRP_MAX_NDIM];
-    double fit_prev = 0.0;
-    for (int sweep = 0; sweep < max_iters; ++sweep) {
-        for (int k = 0; k < ndim; ++k) {
-            for (int m = 0; m < ndim; ++m)
-                cf[m] = factors[m];
-            const int rc = mttkrp_dense_f64(ndim, dims, X, cf, R, k, b.M, stream);
-            if (rc != MTTKRP_OK)
-                return rc;
+    double* mo[MTTKRP_MAX_NDIM];
+    for (int m = 0; m < ndim; ++m) {
+        cf[m] = factors[m];
+        mo[m] = b.M;
+    }
+    // the update of factor k from its MTTKRP in b.M
+    auto update = [&](int k) {
             hipLaunchKernelGGL(hadamard_grams, dim3((unsigned)ceil_div(RR, 256)), dim3(256), 0, st, b.G, ndim, RR, k, b.V);
             hipLaunchKernelGGL(cholesky_lower, dim3(1), dim3(256), (size_t)RR * sizeof(double), st, b.V, R, b.flag);
             hipLaunchKernelGGL(solve_rows, dim3((unsigned)ceil_div(dims[k], 32)), dim3(32),
                                (size_t)(RR + 32 * (R + 1)) * sizeof(double), st, b.V, b.M, dims[k], R, factors[k], b.flag);
             hipLaunchKernelGGL(normalise_columns, dim3(R), dim3(256), 0, st, factors[k], dims[k], R, lambda, b.flag);
             gram(factors[k], dims[k], R, b.gram_ws, b.G + (int64_t)k * RR, st);
+            return (int)MTTKRP_OK;
+    };
+    double fit_prev = 0.0;
+    for (int sweep = 0; sweep < max_iters; ++sweep) {
+        if (shared) {
+            const int rc = shared_sweep<double>(ndim, dims, X, cf, R, mo, b.shared_ws, sp.total, stream, update);
+            if (rc != MTTKRP_OK)
+                return rc;
+        } else {
+            for (int k = 0; k < ndim; ++k) {
+                const int rc = mttkrp_dense_f64(ndim, dims, X, cf, R, k, b.M, stream);
+                if (rc != MTTKRP_OK)
+                    return rc;
+                update(k);
+            }
         }
         // fit terms: b.M still holds the last mode's MTTKRP
         hipLaunchKernelGGL(inner_product_columns, dim3(R), dim3(256), 0, st, b.M, factors[ndim - 1], lambda,
@@ -366,6 +743,22 @@ int mttkrp_cpals_f64(int ndim, const int64_t* dims, const double* X, double* con
         fit_prev = fit;
     }
     return hipGetLastError() == hipSuccess ? MTTKRP_OK : MTTKRP_ERR_DEVICE;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mttkrp_cpals_f64(int ndim, const int64_t* dims, const double* X, double* const* factors, double* lambda,
+                     int R, int max_iters, double tol, int* iters, double* fits, void* stream)
+{
+    return cpals_run(ndim, dims, X, factors, lambda, R, max_iters, tol, iters, fits, stream, false);
+}
+
+int mttkrp_cpals_shared_f64(int ndim, const int64_t* dims, const double* X, double* const* factors, double* lambda,
+                            int R, int max_iters, double tol, int* iters, double* fits, void* stream)
+{
+    return cpals_run(ndim, dims, X, factors, lambda, R, max_iters, tol, iters, fits, stream, true);
 }
 
 }  // extern "C"

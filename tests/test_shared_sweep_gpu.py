@@ -1,0 +1,215 @@
+"""GPU parity of the sweep that shares partial contractions between the modes
+(mttkrp_dense_all_modes_shared_*, mttkrp_contract_leading_*, mttkrp_cpals_shared_f64)
+against the CPU oracles, through the C ABI.
+
+Every mode's result of the shared sweep is the same sum of Eq. (elem) taken in another
+order, so it is compared with the oracle's MTTKRP of that mode at the tolerance of the core
+calls.  The partial contraction over the leading index is, for a 2-way tensor, the MTTKRP
+of its second mode, which the oracle computes by the definition.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_2510_14891_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float64: 1e-12, torch.float32: 1e-5}
+TUNE_KEYS = ("target_items", "max_steps", "max_col_blocks", "rows_col_blocks")
+
+
+@pytest.fixture(scope="module")
+def mt():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2510_14891_amd import binding
+    binding.lib()
+    yield binding
+    for key in TUNE_KEYS:
+        binding.mttkrp_tune_set(key, 0)
+
+
+@pytest.fixture(scope="module")
+def oracle():
+    from oracle import mttkrp_oracle
+    mttkrp_oracle.build()
+    return mttkrp_oracle
+
+
+def make_problem(dims, R, dtype, seed):
+    n = int(np.prod(dims))
+    X = inputs.uniform(seed, n, -1.0, 1.0, dtype=dtype)
+    A = [inputs.uniform(seed + 100 + m, (I, R), -1.0, 1.0, dtype=dtype) for m, I in enumerate(dims)]
+    return X, A
+
+
+def oracle_mode(oracle, X, dims, A, k):
+    return oracle.mttkrp(inputs.as_ndarray_view(X, dims), [a.numpy() for a in A], k)
+
+
+# P, Q, R: several tiles of columns and of output columns with ragged tails, one column, one row,
+# rows that are not a multiple of 16, output columns beyond one chunk
+LEADING = [(130, 77, 16), (1000, 33, 5), (17, 1000, 33), (64, 64, 128), (1, 50, 8), (50, 1, 8),
+           (401, 130, 70), (2500, 40, 1), (333, 2049, 24)]
+
+
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+@pytest.mark.parametrize("P,Q,R", LEADING)
+def test_contract_leading_is_the_second_mode_of_a_matrix(mt, oracle, P, Q, R, dtype):
+    X, A = make_problem((P, Q), R, dtype, seed=300 + P % 97)
+    ref = oracle_mode(oracle, X, (P, Q), A, 1)
+    print("contract_leading P=%d Q=%d R=%d %s" % (P, Q, R, dtype), flush=True)
+    got = mt.mttkrp_contract_leading(X.cuda(), P, Q, A[0].cuda())
+    torch.cuda.synchronize()
+    err = oracle.normwise_rel_err(got.cpu().numpy(), ref)
+    assert err <= TOL[dtype], (P, Q, R, err)
+    assert oracle.rowwise_rel_err(got.cpu().numpy(), ref) <= 50 * TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+def test_contract_leading_with_row_splits_strides_and_reruns(mt, oracle, dtype):
+    """Row splits (partial sums + combine), short items, narrow tiles, leading dimensions of K
+    and T wider than R, and bit-identical reruns."""
+    P, Q, R = 5000, 45, 20
+    X, A = make_problem((P, Q), R, dtype, seed=77)
+    ref = oracle_mode(oracle, X, (P, Q), A, 1)
+    Xd = X.cuda()
+    Kwide = torch.full((P, R + 7), float("nan"), dtype=dtype).cuda()
+    Kwide[:, :R] = A[0].cuda()
+    first = None
+    try:
+        for tune in ({}, {"target_items": 64}, {"max_steps": 16}, {"max_col_blocks": 1}, {"rows_col_blocks": 1},
+                     {"target_items": 20000, "max_col_blocks": 2}):
+            for key in TUNE_KEYS:
+                mt.mttkrp_tune_set(key, tune.get(key, 0))
+            print("contract_leading tune=%s %s" % (tune, dtype), flush=True)
+            Twide = torch.full((Q, R + 3), -7.0, dtype=dtype).cuda()
+            mt.mttkrp_contract_leading(Xd, P, Q, Kwide[:, :R], T_out=Twide[:, :R])
+            torch.cuda.synchronize()
+            got = Twide[:, :R].cpu().numpy()
+            assert oracle.normwise_rel_err(got, ref) <= TOL[dtype], tune
+            assert bool((Twide[:, R:] == -7.0).all()), "columns beyond R must stay untouched"
+            again = mt.mttkrp_contract_leading(Xd, P, Q, Kwide[:, :R])
+            torch.cuda.synchronize()
+            assert np.array_equal(again.cpu().numpy(), got), tune
+            if first is None:
+                first = got
+    finally:
+        for key in TUNE_KEYS:
+            mt.mttkrp_tune_set(key, 0)
+
+
+def test_contract_leading_errors(mt):
+    L = mt.lib()
+    X = torch.zeros(64, dtype=torch.float64).cuda()
+    K = torch.zeros((8, 4), dtype=torch.float64).cuda()
+    T = torch.zeros((8, 4), dtype=torch.float64).cuda()
+    f = L.mttkrp_contract_leading_f64
+    assert f(8, 8, None, K.data_ptr(), 4, 4, T.data_ptr(), 4, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
+    assert f(0, 8, X.data_ptr(), K.data_ptr(), 4, 4, T.data_ptr(), 4, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
+    assert f(8, 8, X.data_ptr(), K.data_ptr(), 3, 4, T.data_ptr(), 4, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
+    assert f(8, 8, X.data_ptr(), K.data_ptr(), 4, 4, T.data_ptr(), 2, None, 0, None) == mt.MTTKRP_ERR_INVALID_ARG
+    assert f(1 << 31, 8, X.data_ptr(), K.data_ptr(), 4, 4, T.data_ptr(), 4, None, 0, None) == mt.MTTKRP_ERR_UNSUPPORTED
+    # a plan with row splits needs its workspace
+    need = L.mttkrp_contract_leading_workspace_bytes(100000, 16, 4, 8)
+    assert need > 0
+    Xb = torch.zeros(100000 * 16, dtype=torch.float64).cuda()
+    Kb = torch.zeros((100000, 4), dtype=torch.float64).cuda()
+    Tb = torch.full((16, 4), 3.0, dtype=torch.float64).cuda()
+    assert f(100000, 16, Xb.data_ptr(), Kb.data_ptr(), 4, 4, Tb.data_ptr(), 4, None, 0, None) == mt.MTTKRP_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert bool((Tb == 3.0).all()), "an error enqueues nothing"
+
+
+SWEEPS = [
+    ((40, 30, 20), 16), ((64, 64, 64), 16), ((13, 7, 5, 9), 3), ((6, 5, 4, 3, 7), 17), ((33, 40), 8),
+    ((129, 12, 39), 10), ((150, 37, 21), 33), ((9, 8, 7, 6, 5, 4), 5), ((1, 20, 30), 4), ((30, 1, 1, 25), 6),
+    ((401, 21, 12, 11), 32), ((2, 3), 1), ((70, 9, 5, 7), 70),
+]
+
+
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+@pytest.mark.parametrize("dims,R", SWEEPS)
+def test_shared_sweep_matches_the_oracle_in_every_mode(mt, oracle, dims, R, dtype):
+    X, A = make_problem(dims, R, dtype, seed=500 + len(dims) * 10 + R)
+    assert mt.mttkrp_dense_all_modes_shared_bytes(dims, R, X.element_size()) > 0
+    print("shared sweep dims=%s R=%d %s" % (dims, R, dtype), flush=True)
+    got = mt.mttkrp_dense_all_modes_shared(X.cuda(), dims, [a.cuda() for a in A])
+    torch.cuda.synchronize()
+    for k in range(len(dims)):
+        ref = oracle_mode(oracle, X, dims, A, k)
+        err = oracle.normwise_rel_err(got[k].cpu().numpy(), ref)
+        assert err <= TOL[dtype], (dims, R, k, err)
+
+
+def test_shared_sweep_at_a_size_of_several_rounds_and_rerun(mt, oracle):
+    """A tensor large enough for row splits, several column chunks and many work items in both
+    passes; compared with the oracle on every mode and with itself bit for bit."""
+    dims, R = (300, 120, 90, 11), 40
+    X, A = make_problem(dims, R, torch.float64, seed=901)
+    Xd, Ad = X.cuda(), [a.cuda() for a in A]
+    got = mt.mttkrp_dense_all_modes_shared(Xd, dims, Ad)
+    torch.cuda.synchronize()
+    first = [g.cpu().numpy().copy() for g in got]
+    again = mt.mttkrp_dense_all_modes_shared(Xd, dims, Ad)
+    torch.cuda.synchronize()
+    plain = mt.mttkrp_dense_all_modes(Xd, dims, Ad)
+    torch.cuda.synchronize()
+    for k in range(len(dims)):
+        ref = oracle_mode(oracle, X, dims, A, k)
+        assert oracle.normwise_rel_err(first[k], ref) <= 1e-12, k
+        assert oracle.rowwise_rel_err(first[k], ref) <= 1e-11, k
+        assert np.array_equal(again[k].cpu().numpy(), first[k]), k
+        assert oracle.normwise_rel_err(plain[k].cpu().numpy(), ref) <= 1e-12, k
+
+
+def test_shared_sweep_unsupported_shapes_and_errors(mt):
+    # intermediates beyond an eighth of the tensor: no supported cut
+    assert mt.mttkrp_dense_all_modes_shared_bytes((401, 201, 12, 501), 1000, 8) == 0
+    assert mt.mttkrp_dense_all_modes_shared_bytes((401, 201, 12, 501), 32, 8) > 0
+    L = mt.lib()
+    import ctypes
+    dims = (ctypes.c_int64 * 3)(8, 8, 8)
+    X = torch.zeros(512, dtype=torch.float64).cuda()
+    A = [torch.zeros((8, 4), dtype=torch.float64).cuda() for _ in range(3)]
+    M = [torch.full((8, 4), 5.0, dtype=torch.float64).cuda() for _ in range(3)]
+    fp = (ctypes.c_void_p * 3)(*[a.data_ptr() for a in A])
+    mp = (ctypes.c_void_p * 3)(*[m.data_ptr() for m in M])
+    need = L.mttkrp_dense_all_modes_shared_bytes(3, dims, 4, 8)
+    ws = torch.zeros(need, dtype=torch.uint8).cuda()
+    f = L.mttkrp_dense_all_modes_shared_f64
+    assert f(3, dims, X.data_ptr(), fp, 4, mp, ws.data_ptr(), need - 1, None) == mt.MTTKRP_ERR_WORKSPACE
+    assert f(3, dims, X.data_ptr(), fp, 4, mp, None, need, None) == mt.MTTKRP_ERR_WORKSPACE
+    assert f(3, dims, None, fp, 4, mp, ws.data_ptr(), need, None) == mt.MTTKRP_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert all(bool((m == 5.0).all()) for m in M), "an error enqueues nothing"
+    assert f(3, dims, X.data_ptr(), fp, 4, mp, ws.data_ptr(), need, None) == mt.MTTKRP_OK
+    torch.cuda.synchronize()
+    assert all(bool((m == 0.0).all()) for m in M)
+
+
+CPALS = [((40, 30, 20), 5, 11), ((17, 9, 6, 5), 3, 12), ((33, 20), 4, 13), ((12, 10, 8, 6, 5), 6, 16)]
+
+
+@pytest.mark.parametrize("dims,R,seed", CPALS)
+def test_cpals_with_shared_sweeps_matches_the_oracle(mt, dims, R, seed):
+    from oracle import cp_als_oracle, mttkrp_oracle
+    mttkrp_oracle.build()
+    n = int(np.prod(dims))
+    X = inputs.normal(seed, n, 0.0, 1.0)
+    A0 = [inputs.uniform(seed + 100 + m, (I, R), 0.0, 1.0) for m, I in enumerate(dims)]
+    sweeps = 5
+    A_ref, lam_ref, fits_ref = cp_als_oracle.cp_als(inputs.as_ndarray_view(X, dims), [a.numpy() for a in A0], sweeps, 0.0)
+    Ad = [a.clone().cuda() for a in A0]
+    print("cp-als (shared sweeps) dims=%s R=%d" % (dims, R), flush=True)
+    lam, fits = mt.mttkrp_cpals(X.cuda(), dims, Ad, sweeps, 0.0, shared=True)
+    torch.cuda.synchronize()
+    assert len(fits) == sweeps
+    np.testing.assert_allclose(fits, fits_ref, rtol=0, atol=1e-10)
+    np.testing.assert_allclose(lam.cpu().numpy(), lam_ref, rtol=1e-9)
+    for m in range(len(dims)):
+        got = Ad[m].cpu().numpy()
+        err = np.linalg.norm(got - A_ref[m]) / np.linalg.norm(A_ref[m])
+        assert err <= 1e-9, (m, err)
