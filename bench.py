@@ -157,6 +157,37 @@ def run_workload(mt, perf_model, w, X, A, steps, warmup):
     return ms_per_step, per_mode, roofline_of(w, kernel_ms, len(main_all), perf_model)
 
 
+def shared_sweep_entry(mt, w, X, A, budget_s=0.12):
+    """The all-modes sweep that shares partial contractions (two passes over X) beside the
+    same d results from d separate calls: wall time per sweep of each, after a warm-up, for
+    about ``budget_s`` seconds each.  Not part of ``value``."""
+    import torch
+    nbytes = mt.mttkrp_dense_all_modes_shared_bytes(w.dims, w.R, w.itemsize)
+    if nbytes == 0:
+        return {"supported": False}
+    M = [torch.empty((I, w.R), dtype=w.torch_dtype, device=X.device) for I in w.dims]
+    out = {"supported": True, "workspace_bytes": nbytes,
+           "workspace_over_x": round(nbytes / (w.numel * w.itemsize), 4)}
+    for label, fn in (("separate", mt.mttkrp_dense_all_modes), ("shared", mt.mttkrp_dense_all_modes_shared)):
+        fn(X, w.dims, A, M_out=M)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn(X, w.dims, A, M_out=M)
+        torch.cuda.synchronize()
+        t1 = max(time.perf_counter() - t0, 1e-5)
+        n = int(min(300, max(3, math.ceil(budget_s / t1))))
+        for _ in range(n):
+            fn(X, w.dims, A, M_out=M)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn(X, w.dims, A, M_out=M)
+        torch.cuda.synchronize()
+        out["ms_" + label] = round(1e3 * (time.perf_counter() - t0) / n, 4)
+    out["speedup"] = round(out["ms_separate"] / out["ms_shared"], 3)
+    return out
+
+
 def config_entry(mt, perf_model, inputs, w, X, A):
     """One element of ``configs``: warm up for about 0.15 s of load (the shader clock settles over
     the first ~0.1 s), then time about 0.25 s worth of steps."""
@@ -178,6 +209,7 @@ def config_entry(mt, perf_model, inputs, w, X, A):
         "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4),
         "value": round(w.ndim * xb / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
         "per_mode": per_mode, "roofline": roofline,
+        "shared_sweep": shared_sweep_entry(mt, w, X, A),
     }
 
 
@@ -371,6 +403,9 @@ def main() -> int:
                "of bytes / stream rate and flops / MFMA rate; the MFMA probe runs 32 wavefronts per CU and "
                "its clock drops further than the kernel's, so a ratio above 1 can occur",
     }
+    # beside the headline (d separate MTTKRPs per step): the same d results from the sweep that
+    # shares partial contractions between the modes
+    out["shared_sweep"] = shared_sweep_entry(mt, w, X, A, budget_s=0.3)
     if args.cpu_budget > 0:
         out["cpu_baseline"] = cpu_baseline(w, X, A, args.cpu_budget, native=False)
         out["cpu_baseline_native"] = cpu_baseline(w, X, A, args.cpu_budget, native=True)
@@ -394,6 +429,9 @@ def main() -> int:
             Ac = inputs.make_factors(wc, device=dev)
             configs.append(config_entry(mt, perf_model, inputs, wc, Xc, Ac))
         out["configs"] = configs
+        out["shared_sweep_speedup_by_workload"] = dict(
+            [(w.name, out["shared_sweep"].get("speedup"))] +
+            [(c["workload"], c["shared_sweep"].get("speedup")) for c in configs])
         out["roofline_frac_by_workload"] = dict(
             [(w.name, roofline["frac"])] + [(c["workload"], c["roofline"]["frac"]) for c in configs])
     print(json.dumps(out), flush=True)
