@@ -308,6 +308,57 @@ def compare_schedules(args) -> int:
     return 0
 
 
+def time_shape(args) -> int:
+    """Every mode of one arbitrary shape (--dims, --rank, --dtype) on random data, as a
+    Markdown row per mode: median kernel time of 15 calls after a warm-up, the plan, and the
+    fraction of the shape's roofline bound."""
+    import torch
+    from paper_2510_14891_amd import binding as mt, perf_model
+    if not torch.cuda.is_available():
+        print("bench.py --shape: no GPU visible", file=sys.stderr)
+        return 3
+    mt.lib()
+    dims = tuple(int(t) for t in args.dims.split(","))
+    R = args.rank
+    dt = torch.float64 if args.dtype == "f64" else torch.float32
+    sb = 8 if args.dtype == "f64" else 4
+    n = math.prod(dims)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1)
+    X = torch.rand(n, dtype=dt, device="cuda", generator=g)
+    A = [torch.rand((I, R), dtype=dt, device="cuda", generator=g) for I in dims]
+    M = [torch.empty((I, R), dtype=dt, device="cuda") for I in dims]
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < 0.3:
+        for k in range(len(dims)):
+            mt.mttkrp_dense(X, dims, A, k, M=M[k])
+        torch.cuda.synchronize()
+    floor = max(perf_model.m_inf(dims, R, sb) / (HBM_PEAK_GBPS * 1e9),
+                2.0 * n * R / (FP_PEAK_TFLOPS[args.dtype] * 1e12)) * 1e3
+    reps = 15
+    print("| shape | R | type | mode | main + combine ms | GB/s of X | TFLOP/s | roofline fraction (main kernel) | rows per wavefront x row blocks | items x steps |")
+    print("|---|---|---|---|---|---|---|---|---|---|")
+    for k in range(len(dims)):
+        for _ in range(3):
+            mt.mttkrp_dense(X, dims, A, k, M=M[k])
+        torch.cuda.synchronize()
+        mt.mttkrp_timing_enable(True)
+        for _ in range(reps):
+            mt.mttkrp_dense(X, dims, A, k, M=M[k])
+        torch.cuda.synchronize()
+        c = mt.mttkrp_timing_count()
+        tm = sorted(mt.mttkrp_timing_get(i)[0] for i in range(c - reps, c))[reps // 2]
+        tc = sorted(mt.mttkrp_timing_get(i)[1] for i in range(c - reps, c))[reps // 2]
+        mt.mttkrp_timing_enable(False)
+        desc = dict(t.split("=") for t in mt.mttkrp_plan_describe(dims, R, k, sb).split())
+        rows = ("%s x %s" % (desc.get("rows_per_wave"), desc.get("row_blocks"))
+                if "rows_per_wave" in desc else "second schedule")
+        print("| %s | %d | %s | %d | %.3f + %.3f | %.0f | %.1f | %.3f | %s | %s x %s |" % (
+            "x".join(str(d) for d in dims), R, args.dtype, k + 1, tm, tc, n * sb / (tm + tc) / 1e6,
+            2.0 * n * R / (tm + tc) / 1e9, floor / tm, rows, desc.get("items"), desc.get("steps_per_item")))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -323,6 +374,7 @@ def main() -> int:
                     help="run only K plain device copies of the X buffer (the known-size "
                          "kernel the rocprofv3 FETCH_SIZE/WRITE_SIZE counters are scaled by)")
     ap.add_argument("--schedules", action="store_true", help="compare the two schedules on --dims/--rank/--mode")
+    ap.add_argument("--shape", action="store_true", help="time every mode of the shape --dims/--rank/--dtype")
     ap.add_argument("--dims", default="16384,2048,64")
     ap.add_argument("--rank", type=int, default=128)
     ap.add_argument("--dtype", default="f64", choices=["f64", "f32"])
@@ -344,6 +396,8 @@ def main() -> int:
     torch.cuda.set_device(dev)
     if args.schedules:
         return compare_schedules(args)
+    if args.shape:
+        return time_shape(args)
     w = inputs.WORKLOADS[args.workload]
     X = inputs.make_tensor(w, device=dev)
     A = inputs.make_factors(w, device=dev)
