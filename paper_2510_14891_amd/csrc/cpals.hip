@@ -12,6 +12,7 @@
 
 namespace {
 
+constexpr int kSmallRank = 64;     // up to here the R x R matrices are handled in one workgroup's LDS
 constexpr int kChunkRows = 64;     // rows of a factor one workgroup turns into a partial Gram matrix
 constexpr int kNormBlocks = 2048;  // partial sums of ||X||^2
 
@@ -228,6 +229,211 @@ __global__ void __launch_bounds__(256) quadratic_form(const double* __restrict__
         out[0] = s;
 }
 
+
+// ---------------------------------------------------------------------------
+// Ranks above 64: the R x R matrices no longer fit the LDS of one workgroup.  Gram matrices,
+// the Cholesky factorisation and the two triangular solves run blocked from global memory,
+// 32 columns at a time, every sum still in a fixed order.
+// ---------------------------------------------------------------------------
+constexpr int kNB = 32;
+
+// G = A^T A: a 16 x 16 tile of G per workgroup, the rows of A in chunks of 16 through LDS, summed
+// in row order.  G(p, q) and G(q, p) add the same products in the same order: G is symmetric bit for bit.
+__global__ void __launch_bounds__(256) gram_tiled(const double* __restrict__ A, int64_t I, int R, double* G)
+{
+    __shared__ double ta[16][17], tb[16][17];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int p0 = blockIdx.y * 16, q0 = blockIdx.x * 16;
+    double s = 0.0;
+    for (int64_t i0 = 0; i0 < I; i0 += 16) {
+        const int64_t i = i0 + ty;
+        ta[ty][tx] = i < I && p0 + tx < R ? A[i * R + p0 + tx] : 0.0;
+        tb[ty][tx] = i < I && q0 + tx < R ? A[i * R + q0 + tx] : 0.0;
+        __syncthreads();
+        const int rows = (int)(I - i0 < 16 ? I - i0 : 16);
+        for (int r = 0; r < rows; ++r)
+            s += ta[r][ty] * tb[r][tx];
+        __syncthreads();
+    }
+    if (p0 + ty < R && q0 + tx < R)
+        G[(int64_t)(p0 + ty) * R + q0 + tx] = s;
+}
+
+// Diagonal block [j0, j0 + nb) of the blocked factorisation: Cholesky factor of the block in
+// LDS by one workgroup, lower triangle written back, the block's upper triangle zeroed.
+__global__ void __launch_bounds__(256) chol_diag(double* V, int R, int j0, int nb, int* flag)
+{
+    __shared__ double B[kNB][kNB + 1];
+    if (flag[0])
+        return;
+    for (int t = threadIdx.x; t < nb * nb; t += 256)
+        B[t / nb][t % nb] = V[(int64_t)(j0 + t / nb) * R + j0 + t % nb];
+    __syncthreads();
+    for (int j = 0; j < nb; ++j) {
+        const double piv = B[j][j];
+        if (!(piv > 0.0)) {
+            if (threadIdx.x == 0)
+                flag[0] = 1;
+            return;   // uniform: every thread sees the same pivot
+        }
+        const double dj = sqrt(piv);
+        __syncthreads();
+        for (int i = j + threadIdx.x; i < nb; i += 256)
+            B[i][j] = i == j ? dj : B[i][j] / dj;
+        __syncthreads();
+        const int n = nb - j - 1;
+        for (int t = threadIdx.x; t < n * n; t += 256) {
+            const int i = j + 1 + t / n, c = j + 1 + t % n;
+            if (c <= i)
+                B[i][c] -= B[i][j] * B[c][j];
+        }
+        __syncthreads();
+    }
+    for (int t = threadIdx.x; t < nb * nb; t += 256) {
+        const int r = t / nb, c = t % nb;
+        V[(int64_t)(j0 + r) * R + j0 + c] = c <= r ? B[r][c] : 0.0;
+    }
+}
+
+// The nb x nb triangle L11 = V[j0 .., j0 ..] into LDS (all of the workgroup's threads).
+__device__ __forceinline__ void load_diag_block(const double* __restrict__ V, int R, int j0, int nb, double (*B)[kNB + 1])
+{
+    for (int t = threadIdx.x; t < kNB * kNB; t += blockDim.x) {
+        const int r = t / kNB, c = t % kNB;
+        B[r][c] = r < nb && c < nb ? V[(int64_t)(j0 + r) * R + j0 + c] : (r == c ? 1.0 : 0.0);
+    }
+    __syncthreads();
+}
+
+// Rows [r0, r1) of the matrix Y (leading dimension R), columns [j0, j0 + nb): every row is solved
+// against L11 (forward: y_c = (y_c - sum_{q < c} L11(c, q) y_q) / L11(c, c), c ascending) or its
+// transpose (backward: x_c = (x_c - sum_{q > c} L11(q, c) x_q) / L11(c, c), c descending); one
+// thread per row, the row's unknowns in LDS.
+constexpr int kSolveThreads = 128;
+template <bool FORWARD>
+__global__ void __launch_bounds__(kSolveThreads)
+solve_diag_rows(const double* __restrict__ L, int R, int j0, int nb, double* Y, int64_t r0, int64_t r1, const int* flag)
+{
+    __shared__ double B[kNB][kNB + 1];
+    __shared__ double ys[kNB][kSolveThreads];
+    if (flag[0])
+        return;
+    load_diag_block(L, R, j0, nb, B);
+    const int64_t row = r0 + (int64_t)blockIdx.x * kSolveThreads + threadIdx.x;
+    if (row >= r1)
+        return;
+    const int tid = threadIdx.x;
+    for (int c = 0; c < nb; ++c)
+        ys[c][tid] = Y[row * R + j0 + c];
+    if (FORWARD) {
+        for (int c = 0; c < nb; ++c) {
+            double v = ys[c][tid];
+            for (int q = 0; q < c; ++q)
+                v -= B[c][q] * ys[q][tid];
+            ys[c][tid] = v / B[c][c];
+        }
+    } else {
+        for (int c = nb - 1; c >= 0; --c) {
+            double v = ys[c][tid];
+            for (int q = nb - 1; q > c; --q)
+                v -= B[q][c] * ys[q][tid];
+            ys[c][tid] = v / B[c][c];
+        }
+    }
+    for (int c = 0; c < nb; ++c)
+        Y[row * R + j0 + c] = ys[c][tid];
+}
+
+// Y(row, c) -= sum_{q < nb} S(row, q) * W(c, q) for rows [r0, r1) and columns [c0, c1), a 16 x 16
+// tile per workgroup.  S(row, q) = Y(row, j0 + q); W(c, q) = L(c, j0 + q) (TRANS = false: the
+// columns below a block of the forward solve and of the factorisation's trailing update) or
+// L(j0 + q, c) (TRANS = true: the columns before a block of the backward solve).  LOWER: only
+// entries with c <= row are touched (the factorisation keeps the lower triangle).
+template <bool TRANS, bool LOWER>
+__global__ void __launch_bounds__(256)
+update_tile(const double* __restrict__ L, int R, int j0, int nb, double* Y, int64_t r0, int64_t r1, int c0, int c1,
+            const int* flag)
+{
+    __shared__ double S[16][kNB + 1], W[16][kNB + 1];
+    if (flag[0])
+        return;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int64_t rt = r0 + (int64_t)blockIdx.y * 16;
+    const int ct = c0 + blockIdx.x * 16;
+    if (LOWER && ct > rt + 15)
+        return;      // a tile above the diagonal
+    for (int t = threadIdx.x; t < 16 * kNB; t += 256) {
+        const int a = t / kNB, q = t % kNB;
+        S[a][q] = q < nb && rt + a < r1 ? Y[(rt + a) * R + j0 + q] : 0.0;
+        double w = 0.0;
+        if (q < nb && ct + a < c1)
+            w = TRANS ? L[(int64_t)(j0 + q) * R + ct + a] : L[(int64_t)(ct + a) * R + j0 + q];
+        W[a][q] = w;
+    }
+    __syncthreads();
+    const int64_t row = rt + ty;
+    const int c = ct + tx;
+    if (row >= r1 || c >= c1 || (LOWER && c > row))
+        return;
+    double s = 0.0;
+#pragma unroll
+    for (int q = 0; q < kNB; ++q)
+        s += S[ty][q] * W[tx][q];
+    Y[row * R + c] -= s;
+}
+
+// dst = src (n values) unless the factorisation failed.
+__global__ void __launch_bounds__(256) copy_unless_flag(const double* __restrict__ src, double* dst, int64_t n, const int* flag)
+{
+    if (flag[0])
+        return;
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e < n)
+        dst[e] = src[e];
+}
+
+// V := its Cholesky factor (lower triangle; the strict upper triangle keeps stale values that
+// nothing reads), block column by block column: factor the diagonal block, solve the panel below
+// it (rows of V against L11), update the trailing lower triangle.
+void cholesky_blocked(double* V, int R, int* flag, hipStream_t st)
+{
+    for (int j0 = 0; j0 < R; j0 += kNB) {
+        const int nb = R - j0 < kNB ? R - j0 : kNB;
+        hipLaunchKernelGGL(chol_diag, dim3(1), dim3(256), 0, st, V, R, j0, nb, flag);
+        const int j1 = j0 + nb;
+        if (j1 >= R)
+            break;
+        const int below = R - j1;
+        hipLaunchKernelGGL((solve_diag_rows<true>), dim3((unsigned)ceil_div(below, kSolveThreads)), dim3(kSolveThreads), 0, st,
+                           (const double*)V, R, j0, nb, V, (int64_t)j1, (int64_t)R, (const int*)flag);
+        const unsigned nt = (unsigned)ceil_div(below, 16);
+        hipLaunchKernelGGL((update_tile<false, true>), dim3(nt, nt), dim3(256), 0, st,
+                           (const double*)V, R, j0, nb, V, (int64_t)j1, (int64_t)R, j1, R, (const int*)flag);
+    }
+}
+
+// Rows of Y (I x R, in place) := Y V^{-1} with V = L L^T: forward against L block by block, then
+// backward against L^T.
+void solve_blocked(const double* L, int R, double* Y, int64_t I, const int* flag, hipStream_t st)
+{
+    const unsigned rb = (unsigned)ceil_div(I, kSolveThreads), rt = (unsigned)ceil_div(I, 16);
+    for (int j0 = 0; j0 < R; j0 += kNB) {
+        const int nb = R - j0 < kNB ? R - j0 : kNB;
+        hipLaunchKernelGGL((solve_diag_rows<true>), dim3(rb), dim3(kSolveThreads), 0, st, L, R, j0, nb, Y, (int64_t)0, I, flag);
+        const int j1 = j0 + nb;
+        if (j1 < R)
+            hipLaunchKernelGGL((update_tile<false, false>), dim3((unsigned)ceil_div(R - j1, 16), rt), dim3(256), 0, st,
+                               L, R, j0, nb, Y, (int64_t)0, I, j1, R, flag);
+    }
+    for (int j0 = (R - 1) / kNB * kNB; j0 >= 0; j0 -= kNB) {
+        const int nb = R - j0 < kNB ? R - j0 : kNB;
+        hipLaunchKernelGGL((solve_diag_rows<false>), dim3(rb), dim3(kSolveThreads), 0, st, L, R, j0, nb, Y, (int64_t)0, I, flag);
+        if (j0 > 0)
+            hipLaunchKernelGGL((update_tile<true, false>), dim3((unsigned)ceil_div(j0, 16), rt), dim3(256), 0, st,
+                               L, R, j0, nb, Y, (int64_t)0, I, 0, j0, flag);
+    }
+}
+
 struct Buffers {
     double* M = nullptr;        // max_n I_n x R
     double* G = nullptr;        // d x R x R Gram matrices
@@ -247,6 +453,11 @@ struct Buffers {
 
 void gram(const double* A, int64_t I, int R, double* ws, double* G, hipStream_t st)
 {
+    if (R > kSmallRank) {
+        const unsigned nt = (unsigned)ceil_div(R, 16);
+        hipLaunchKernelGGL(gram_tiled, dim3(nt, nt), dim3(256), 0, st, A, I, R, G);
+        return;
+    }
     const int n_chunks = (int)ceil_div(I, kChunkRows);
     hipLaunchKernelGGL(gram_partial, dim3(n_chunks), dim3(256), (size_t)kChunkRows * R * sizeof(double), st, A, I, R, ws);
     hipLaunchKernelGGL(gram_reduce, dim3((unsigned)ceil_div(R * R, 256)), dim3(256), 0, st, ws, n_chunks, R * R, G);
@@ -644,6 +855,7 @@ int cpals_run(int ndim, const int64_t* dims, const double* X, double* const* fac
         return MTTKRP_ERR_INVALID_ARG;
     if (ndim > MTTKRP_MAX_NDIM || R > MTTKRP_CPALS_MAX_RANK)
         return MTTKRP_ERR_UNSUPPORTED;
+    const bool big = R > kSmallRank;
     int64_t N = 1, max_I = 1;
     for (int m = 0; m < ndim; ++m) {
         if (dims[m] < 1 || !factors[m])
@@ -656,6 +868,8 @@ int cpals_run(int ndim, const int64_t* dims, const double* X, double* const* fac
         if (dims[m] > max_I)
             max_I = dims[m];
     }
+    if (big && max_I > (int64_t)65535 * 16)
+        return MTTKRP_ERR_UNSUPPORTED;     // the blocked solves' grids
     *iters = 0;
     hipStream_t st = (hipStream_t)stream;
     const int RR = R * R;
@@ -666,11 +880,11 @@ int cpals_run(int ndim, const int64_t* dims, const double* X, double* const* fac
         shared = false;
     if (shared && hipMalloc(&b.shared_ws, sp.total) != hipSuccess)
         return MTTKRP_ERR_DEVICE;
-    const int64_t max_chunks = ceil_div(max_I, kChunkRows);
+    const int64_t max_chunks = big ? 1 : ceil_div(max_I, kChunkRows);
     if (hipMalloc(&b.M, (size_t)max_I * R * sizeof(double)) != hipSuccess ||
         hipMalloc(&b.G, (size_t)ndim * RR * sizeof(double)) != hipSuccess ||
         hipMalloc(&b.V, (size_t)RR * sizeof(double)) != hipSuccess ||
-        hipMalloc(&b.gram_ws, (size_t)max_chunks * RR * sizeof(double)) != hipSuccess ||
+        hipMalloc(&b.gram_ws, (size_t)max_chunks * (big ? 1 : RR) * sizeof(double)) != hipSuccess ||
         hipMalloc(&b.partial, (size_t)(kNormBlocks + R) * sizeof(double)) != hipSuccess ||
         hipMalloc(&b.scalars, 3 * sizeof(double)) != hipSuccess ||
         hipMalloc(&b.flag, sizeof(int)) != hipSuccess)
@@ -695,9 +909,19 @@ int cpals_run(int ndim, const int64_t* dims, const double* X, double* const* fac
     // the update of factor k from its MTTKRP in b.M
     auto update = [&](int k) {
             hipLaunchKernelGGL(hadamard_grams, dim3((unsigned)ceil_div(RR, 256)), dim3(256), 0, st, b.G, ndim, RR, k, b.V);
-            hipLaunchKernelGGL(cholesky_lower, dim3(1), dim3(256), (size_t)RR * sizeof(double), st, b.V, R, b.flag);
-            hipLaunchKernelGGL(solve_rows, dim3((unsigned)ceil_div(dims[k], 32)), dim3(32),
-                               (size_t)(RR + 32 * (R + 1)) * sizeof(double), st, b.V, b.M, dims[k], R, factors[k], b.flag);
+            if (big) {
+                // the rows of M go to A_k (unless the factorisation failed) and are solved there in
+                // place: M itself stays for the fit
+                cholesky_blocked(b.V, R, b.flag, st);
+                const int64_t n = dims[k] * (int64_t)R;
+                hipLaunchKernelGGL(copy_unless_flag, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st,
+                                   (const double*)b.M, factors[k], n, (const int*)b.flag);
+                solve_blocked(b.V, R, factors[k], dims[k], b.flag, st);
+            } else {
+                hipLaunchKernelGGL(cholesky_lower, dim3(1), dim3(256), (size_t)RR * sizeof(double), st, b.V, R, b.flag);
+                hipLaunchKernelGGL(solve_rows, dim3((unsigned)ceil_div(dims[k], 32)), dim3(32),
+                                   (size_t)(RR + 32 * (R + 1)) * sizeof(double), st, b.V, b.M, dims[k], R, factors[k], b.flag);
+            }
             hipLaunchKernelGGL(normalise_columns, dim3(R), dim3(256), 0, st, factors[k], dims[k], R, lambda, b.flag);
             gram(factors[k], dims[k], R, b.gram_ws, b.G + (int64_t)k * RR, st);
             return (int)MTTKRP_OK;

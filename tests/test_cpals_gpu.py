@@ -66,6 +66,46 @@ def test_cpals_matches_the_oracle(mt, dims, R, seed):
         assert err <= 1e-9, (m, err)
 
 
+# Ranks above 64 take the blocked Gram / Cholesky / triangular-solve kernels (32 columns at a
+# time): just above the switch, a multiple of the block, partial last blocks, a short mode.
+LARGE_RANK = [((100, 70, 66), 65, 31), ((120, 110, 100), 96, 32), ((90, 85, 80), 80, 33), ((72, 71, 70, 5), 70, 34),
+              ((40, 150, 140), 130, 35)]
+
+
+@pytest.mark.parametrize("dims,R,seed", LARGE_RANK)
+@pytest.mark.parametrize("shared", [False, True])
+def test_cpals_large_rank_matches_the_oracle(mt, dims, R, seed, shared):
+    from oracle import cp_als_oracle, mttkrp_oracle
+    mttkrp_oracle.build()
+    X, A0 = problem(dims, R, seed)
+    sweeps = 3
+    A_ref, lam_ref, fits_ref = cp_als_oracle.cp_als(inputs.as_ndarray_view(X, dims), [a.numpy() for a in A0], sweeps, 0.0)
+    Ad = [a.clone().cuda() for a in A0]
+    print("cp-als large rank dims=%s R=%d shared=%s" % (dims, R, shared), flush=True)
+    lam, fits = mt.mttkrp_cpals(X.cuda(), dims, Ad, sweeps, 0.0, shared=shared)
+    torch.cuda.synchronize()
+    assert len(fits) == sweeps
+    np.testing.assert_allclose(fits, fits_ref, rtol=0, atol=1e-9)
+    np.testing.assert_allclose(lam.cpu().numpy(), lam_ref, rtol=1e-7)
+    for m in range(len(dims)):
+        got = Ad[m].cpu().numpy()
+        err = np.linalg.norm(got - A_ref[m]) / np.linalg.norm(A_ref[m])
+        assert err <= 1e-7, (m, err)
+
+
+def test_cpals_large_rank_singular_gram_is_reported(mt):
+    dims, R = (80, 75, 70), 72
+    X, A0 = problem(dims, R, 36)
+    Ad = [a.clone().cuda() for a in A0]
+    Ad[1][:, 40] = 0.0
+    before = Ad[0].clone()
+    with pytest.raises(mt.MttkrpError) as e:
+        mt.mttkrp_cpals(X.cuda(), dims, Ad, 2, 0.0)
+    assert e.value.status == mt.MTTKRP_ERR_NUMERICAL
+    torch.cuda.synchronize()
+    assert torch.equal(Ad[0], before)
+
+
 def test_cpals_tolerance_stop_and_reproducibility(mt):
     from oracle import cp_als_oracle, mttkrp_oracle
     mttkrp_oracle.build()
@@ -116,7 +156,7 @@ def test_cpals_errors(mt):
     X, A0 = problem(dims, 3, 51)
     Xd = X.cuda()
     with pytest.raises(mt.MttkrpError) as e:
-        big = [torch.ones((I, 65), dtype=torch.float64, device="cuda") for I in dims]
+        big = [torch.ones((I, 2049), dtype=torch.float64, device="cuda") for I in dims]
         mt.mttkrp_cpals(Xd, dims, big, 2, 0.0)
     assert e.value.status == mt.MTTKRP_ERR_UNSUPPORTED
     # a zero column makes the Gram Hadamard product singular: reported, not a crash or a NaN
