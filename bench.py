@@ -188,7 +188,7 @@ def shared_sweep_entry(mt, w, X, A, budget_s=0.12):
     return out
 
 
-def config_entry(mt, perf_model, inputs, w, X, A):
+def config_entry(mt, perf_model, inputs, w, X, A, sweep=True):
     """One element of ``configs``: warm up for about 0.15 s of load (the shader clock settles over
     the first ~0.1 s), then time about 0.25 s worth of steps."""
     import torch
@@ -209,7 +209,7 @@ def config_entry(mt, perf_model, inputs, w, X, A):
         "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4),
         "value": round(w.ndim * xb / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
         "per_mode": per_mode, "roofline": roofline,
-        "shared_sweep": shared_sweep_entry(mt, w, X, A),
+        "shared_sweep": shared_sweep_entry(mt, w, X, A) if sweep else None,
     }
 
 
@@ -368,6 +368,8 @@ def main() -> int:
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the `configs` array (the other configurations, measured after the main one)")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip the `shared_sweep` objects (the all-modes sweeps timed beside the headline)")
     ap.add_argument("--cpu-budget", type=float, default=10.0,
                     help="seconds of oracle time for each of the two CPU baselines (0 = skip)")
     ap.add_argument("--copy-only", action="store_true",
@@ -459,7 +461,8 @@ def main() -> int:
     }
     # beside the headline (d separate MTTKRPs per step): the same d results from the sweep that
     # shares partial contractions between the modes
-    out["shared_sweep"] = shared_sweep_entry(mt, w, X, A, budget_s=0.3)
+    if not args.no_sweep:
+        out["shared_sweep"] = shared_sweep_entry(mt, w, X, A, budget_s=0.3)
     if args.cpu_budget > 0:
         out["cpu_baseline"] = cpu_baseline(w, X, A, args.cpu_budget, native=False)
         out["cpu_baseline_native"] = cpu_baseline(w, X, A, args.cpu_budget, native=True)
@@ -481,11 +484,12 @@ def main() -> int:
                 Xc = inputs.make_tensor(wc, device=dev)
                 cache_key = key
             Ac = inputs.make_factors(wc, device=dev)
-            configs.append(config_entry(mt, perf_model, inputs, wc, Xc, Ac))
+            configs.append(config_entry(mt, perf_model, inputs, wc, Xc, Ac, sweep=not args.no_sweep))
         out["configs"] = configs
-        out["shared_sweep_speedup_by_workload"] = dict(
-            [(w.name, out["shared_sweep"].get("speedup"))] +
-            [(c["workload"], c["shared_sweep"].get("speedup")) for c in configs])
+        if not args.no_sweep:
+            out["shared_sweep_speedup_by_workload"] = dict(
+                [(w.name, out["shared_sweep"].get("speedup"))] +
+                [(c["workload"], c["shared_sweep"].get("speedup")) for c in configs])
         out["roofline_frac_by_workload"] = dict(
             [(w.name, roofline["frac"])] + [(c["workload"], c["roofline"]["frac"]) for c in configs])
     print(json.dumps(out), flush=True)
