@@ -128,3 +128,34 @@ def test_tile_volume_matches_the_oracle(mt):
     assert L.mttkrp_tile_volume(3, d3, 0, 8, 1, ctypes.byref(w), ctypes.byref(w)) == mt.MTTKRP_ERR_INVALID_ARG
     assert L.mttkrp_tile_volume(1, d3, 1024, 8, 1, ctypes.byref(w), ctypes.byref(w)) == mt.MTTKRP_ERR_INVALID_ARG
     assert L.mttkrp_ablation_f64(9, 3, d3, None, None, 4, 0, 1, None, None) == mt.MTTKRP_ERR_INVALID_ARG
+
+
+def test_shared_sweep_and_leading_contraction_plans(mt):
+    """Host arithmetic of the sweep that shares partial contractions: the workspace query is
+    positive where a cut fits an eighth of the tensor (or 64 MiB), 0 where none does, never
+    more than that bound, and the leading contraction only asks for partial sums when its
+    columns alone cannot fill the chip."""
+    L = mt.lib()
+    NO = ctypes.c_size_t(-1).value
+    for dims, R, sb in (((1024, 1024, 512), 32, 8), ((192,) * 4, 16, 8), ((48,) * 5, 64, 4),
+                        ((16384, 2048, 64), 4, 8), ((16384, 2048, 64), 128, 8), ((401, 201, 12, 501), 32, 8),
+                        ((129, 129, 129, 12, 39), 32, 8), ((64, 64, 64), 16, 8), ((5, 4), 3, 8)):
+        n = 1
+        for d in dims:
+            n *= d
+        b = mt.mttkrp_dense_all_modes_shared_bytes(dims, R, sb)
+        assert 0 < b <= max(n * sb // 8, 64 << 20), (dims, R, b)
+    # intermediates far beyond the tensor: not supported, the caller runs d separate passes
+    assert mt.mttkrp_dense_all_modes_shared_bytes((401, 201, 12, 501), 1000, 8) == 0
+    assert mt.mttkrp_dense_all_modes_shared_bytes((4096, 8), 2000, 8) == 0 or \
+        mt.mttkrp_dense_all_modes_shared_bytes((4096, 8), 2000, 8) <= 64 << 20
+    # invalid arguments
+    assert mt.mttkrp_dense_all_modes_shared_bytes((8, 0, 8), 4, 8) == 0
+    assert mt.mttkrp_dense_all_modes_shared_bytes((8, 8), 4, 2) == 0
+    f = L.mttkrp_contract_leading_workspace_bytes
+    assert f(1024, 1024 * 512, 32, 8) == 0            # many columns: no row splits, no partial sums
+    assert f(16384, 131072, 128, 8) == 0
+    assert f(100000, 16, 4, 8) > 0                    # one column tile: rows are split
+    assert f(100000, 16, 4, 8) % (16 * 4 * 8) == 0    # [column][split][R] values
+    assert f(0, 16, 4, 8) == NO and f(16, 0, 4, 8) == NO and f(16, 16, 0, 8) == NO and f(16, 16, 4, 3) == NO
+    assert f(1 << 31, 16, 4, 8) == NO and f(16, 1 << 31, 4, 8) == NO
