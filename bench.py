@@ -359,6 +359,40 @@ def time_shape(args) -> int:
     return 0
 
 
+def time_leading(args) -> int:
+    """The partial contraction over the leading index (mttkrp_contract_leading_*) on a P x Q
+    matrix of random data (--dims P,Q, --rank, --dtype): one Markdown row, wall clock of 20 calls
+    between two synchronisations after 20 warm-up calls."""
+    import torch
+    from paper_2510_14891_amd import binding as mt
+    if not torch.cuda.is_available():
+        print("bench.py --leading: no GPU visible", file=sys.stderr)
+        return 3
+    mt.lib()
+    P, Q = (int(t) for t in args.dims.split(","))
+    R = args.rank
+    dt = torch.float64 if args.dtype == "f64" else torch.float32
+    sb = 8 if args.dtype == "f64" else 4
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1)
+    X = torch.rand(P * Q, dtype=dt, device="cuda", generator=g)
+    K = torch.rand((P, R), dtype=dt, device="cuda", generator=g)
+    T = torch.empty((Q, R), dtype=dt, device="cuda")
+    for _ in range(20):
+        mt.mttkrp_contract_leading(X, P, Q, K, T_out=T)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(20):
+        mt.mttkrp_contract_leading(X, P, Q, K, T_out=T)
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / 20
+    print("| P x Q | R | type | ms | GB/s of X | TFLOP/s |")
+    print("|---|---|---|---|---|---|")
+    print("| %d x %d | %d | %s | %.3f | %.0f | %.1f |" % (P, Q, R, args.dtype, ms, P * Q * sb / ms / 1e6,
+                                                         2.0 * P * Q * R / ms / 1e9))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -377,6 +411,8 @@ def main() -> int:
                          "kernel the rocprofv3 FETCH_SIZE/WRITE_SIZE counters are scaled by)")
     ap.add_argument("--schedules", action="store_true", help="compare the two schedules on --dims/--rank/--mode")
     ap.add_argument("--shape", action="store_true", help="time every mode of the shape --dims/--rank/--dtype")
+    ap.add_argument("--leading", action="store_true",
+                    help="time the partial contraction over the leading index on --dims P,Q / --rank / --dtype")
     ap.add_argument("--dims", default="16384,2048,64")
     ap.add_argument("--rank", type=int, default=128)
     ap.add_argument("--dtype", default="f64", choices=["f64", "f32"])
@@ -400,6 +436,8 @@ def main() -> int:
         return compare_schedules(args)
     if args.shape:
         return time_shape(args)
+    if args.leading:
+        return time_leading(args)
     w = inputs.WORKLOADS[args.workload]
     X = inputs.make_tensor(w, device=dev)
     A = inputs.make_factors(w, device=dev)
