@@ -17,6 +17,10 @@ result.  What is compared per (workload, mode):
   no arithmetic) and handed to the oracle as a tensor with fewer entries in
   mode k.
 
+Where the shape is supported, the results of the sweep that shares partial
+contractions between the modes (mttkrp_dense_all_modes_shared_*) are held to the
+same oracle values.
+
 The error is the normwise relative error over the compared rows, tolerance
 1e-12 (fp64) / 1e-5 (fp32), and the worst row's own relative error is held to
 the same tolerance.  For the sampled case two further checks touch every entry
@@ -100,6 +104,14 @@ def check_workload(mt, oracle, name):
     A = inputs.make_factors(w, device="cuda")
     A_host = [a.cpu().numpy() for a in A]
     X_host = None
+    # the same d results from the sweep that shares partial contractions (two passes over X),
+    # where the shape is supported; compared below with the same oracle values
+    shared = None
+    if mt.mttkrp_dense_all_modes_shared_bytes(w.dims, w.R, w.itemsize) > 0:
+        shared = [m.cpu().numpy() for m in mt.mttkrp_dense_all_modes_shared(X, w.dims, A)]
+        torch.cuda.synchronize()
+        mt._scratch_buffers.clear()             # the sweep's workspace is not needed any more
+        torch.cuda.empty_cache()
     for k in range(w.ndim):
         plan = mt.mttkrp_plan_describe(w.dims, w.R, k, w.itemsize)
         print("full-size %s mode %d: %s" % (name, k + 1, plan), flush=True)
@@ -127,6 +139,13 @@ def check_workload(mt, oracle, name):
               % (what, err, row_err, time.perf_counter() - t0), flush=True)
         assert err <= TOL[w.dtype], (name, k, err)
         assert row_err <= TOL[w.dtype], (name, k, row_err)
+        if shared is not None:
+            got_s = shared[k] if rows is None else shared[k][rows]
+            err_s = oracle.normwise_rel_err(got_s, ref)
+            row_s = oracle.rowwise_rel_err(got_s, ref)
+            print("   shared sweep: normwise rel err %.3e, worst row %.3e" % (err_s, row_s), flush=True)
+            assert err_s <= TOL[w.dtype], (name, k, err_s)
+            assert row_s <= TOL[w.dtype], (name, k, row_s)
     del X
     torch.cuda.empty_cache()
 
