@@ -213,3 +213,65 @@ def test_cpals_with_shared_sweeps_matches_the_oracle(mt, dims, R, seed):
         got = Ad[m].cpu().numpy()
         err = np.linalg.norm(got - A_ref[m]) / np.linalg.norm(A_ref[m])
         assert err <= 1e-9, (m, err)
+
+
+def test_seeded_random_shapes_shared_sweep_and_leading_contraction(mt, oracle):
+    """Two hundred seeded random problems (2 to 7 modes, extents 1 to 2053, R 1 to 200, both data
+    types, planner settings that change the tiles and the row splits): every mode of the shared
+    sweep and one leading contraction per problem against the oracle.  The tolerance is the one of
+    the core calls, widened only for outputs that are ill-conditioned sums: with
+    c = ||MTTKRP of the absolute values|| / ||MTTKRP|| the forward error of any summation order is
+    bounded by a small multiple of u c, so 8 u c is allowed where that exceeds the tolerance
+    (a 1 x 1 fp32 output whose 992 terms cancel to 4e-4 of their absolute sum is such a case)."""
+    rng = np.random.default_rng(20240611)
+    I0s = (1, 2, 5, 15, 16, 17, 31, 48, 63, 64, 65, 100, 129, 200, 257, 300, 401, 520, 1000, 2053)
+    Is = (1, 2, 3, 4, 5, 7, 9, 12, 13, 16, 17, 31, 33, 40, 64)
+    Rs = (1, 2, 3, 4, 7, 8, 10, 16, 17, 24, 32, 33, 48, 50, 64, 65, 100, 128, 130, 200)
+    tunes = ({}, {}, {}, {"target_items": 50000}, {"target_items": 300}, {"max_steps": 3}, {"max_col_blocks": 1},
+             {"max_col_blocks": 3}, {"rows_col_blocks": 1}, {"rows_col_blocks": 2}, {"target_items": 20000, "max_steps": 16})
+    unit = {torch.float64: 2.0 ** -53, torch.float32: 2.0 ** -24}
+    try:
+        for case in range(200):
+            d = int(rng.choice((2, 3, 3, 3, 4, 4, 5, 6, 7)))
+            dims = [int(rng.choice(I0s))] + [int(rng.choice(Is)) for _ in range(d - 1)]
+            if rng.random() < 0.3:
+                rng.shuffle(dims)
+            while int(np.prod(dims)) > 300_000:
+                i = int(np.argmax(dims))
+                dims[i] = max(1, dims[i] // 2)
+            R = int(rng.choice(Rs))
+            dtype = torch.float64 if rng.random() < 0.6 else torch.float32
+            tune = tunes[int(rng.integers(len(tunes)))]
+            X, A = make_problem(tuple(dims), R, dtype, seed=9000 + case)
+            Xd, Ad = X.cuda(), [a.cuda() for a in A]
+            Xn, An = inputs.as_ndarray_view(X, dims), [a.numpy() for a in A]
+            for key in TUNE_KEYS:
+                mt.mttkrp_tune_set(key, tune.get(key, 0))
+            print("random shared case %d dims=%s R=%d %s tune=%s" % (case, dims, R, dtype, tune), flush=True)
+
+            def allowed(ref, Xabs, Aabs, k):
+                c = np.linalg.norm(oracle.mttkrp(Xabs, Aabs, k)) / max(np.linalg.norm(ref), 1e-300)
+                return max(TOL[dtype], 8.0 * unit[dtype] * c)
+
+            if mt.mttkrp_dense_all_modes_shared_bytes(dims, R, X.element_size()) > 0:
+                Ms = mt.mttkrp_dense_all_modes_shared(Xd, dims, Ad)
+                torch.cuda.synchronize()
+                for k in range(d):
+                    ref = oracle.mttkrp(Xn, An, k)
+                    err = oracle.normwise_rel_err(Ms[k].cpu().numpy(), ref)
+                    if not err <= TOL[dtype]:
+                        assert err <= allowed(ref, np.abs(Xn), [np.abs(a) for a in An], k), (case, dims, R, k, err)
+            s = 1 + int(rng.integers(d - 1))
+            P = int(np.prod(dims[:s]))
+            Q = int(np.prod(dims)) // P
+            K = inputs.uniform(9500 + case, (P, R), -1.0, 1.0, dtype=dtype)
+            T = mt.mttkrp_contract_leading(Xd, P, Q, K.cuda())
+            torch.cuda.synchronize()
+            X2 = np.reshape(X.numpy(), (P, Q), order="F")
+            ref = oracle.mttkrp(X2, [K.numpy(), None], 1)
+            err = oracle.normwise_rel_err(T.cpu().numpy(), ref)
+            if not err <= TOL[dtype]:
+                assert err <= allowed(ref, np.abs(X2), [np.abs(K.numpy()), None], 1), (case, P, Q, R, err)
+    finally:
+        for key in TUNE_KEYS:
+            mt.mttkrp_tune_set(key, 0)
