@@ -273,6 +273,9 @@ int mttkrp_timing_last(float* stream_ms, float* combine_ms);
  *   "nt_loads"      1 = never use non-temporal tensor loads, 0 = chosen by alignment
  *   "fuse_bytes"    largest product matrix (bytes) for which two adjacent modes
  *                   are fused into one (default 8 MiB; 1 = never fuse)
+ *   "pair_rows"     k = 1 only: 1 = take the pairs (i_0, i_1) as the rows whenever I_0 >= 64
+ *                   (no padded row blocks; the epilogue sums each tile per i_1), 2 = never,
+ *                   0 = when the padded row blocks of I_0 alone would waste more than 3 %
  *   "contract_rows" schedule for k != 0: 1 = contract over mode 0 (rows) whenever the
  *                   other modes' entries number at most 1024, 2 = never, 0 = chosen by
  *                   the planner (those entries few, under 128, mode 0 at least eight

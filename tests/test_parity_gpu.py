@@ -31,7 +31,7 @@ def mt():
 
 
 TUNE_KEYS = ("row_blocks", "target_items", "max_steps", "xcd_remap", "ws_percent",
-             "max_col_blocks", "first_group", "deep", "waves_per_simd", "nt_loads", "fuse_bytes", "inner_splits", "contract_rows", "rows_col_blocks", "linear")
+             "max_col_blocks", "first_group", "deep", "waves_per_simd", "nt_loads", "fuse_bytes", "inner_splits", "contract_rows", "rows_col_blocks", "linear", "pair_rows")
 
 
 def make_problem(dims, R, dtype, seed, dist=("uniform", -1.0, 1.0)):
@@ -499,6 +499,64 @@ def test_fused_row_modes(mt, oracle, dtype):
         assert "fused_rows=0" in mt.mttkrp_plan_describe((19, 5, 9, 300), 20, 2, 8)
     finally:
         mt.mttkrp_tune_set("fuse_bytes", 0)
+
+
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+def test_paired_rows_for_mode_1(mt, oracle, dtype):
+    """k = 1 with the pairs (i_0, i_1) taken as the rows and each tile's rows summed per value of
+    i_1: shapes the planner picks it for (I_0 not near a multiple of the row tiles), and forced on
+    for extents where the ranges of i_0 begin on tile boundaries (64, 128), just off them (65, 127),
+    with few and many column entries (one split and many), tiles of 16 to 64 rows, ragged R, one
+    and several chunks of output columns; plain call, leading dimensions with NaN padding, lambda
+    and beta, and twice in a row in one workspace (unwritten slots are cleared at every call)."""
+    sb = 8 if dtype == torch.float64 else 4
+    picked = (((401, 21, 12, 11), 32), ((129, 9, 40, 7), 10), ((100, 5, 300), 7), ((70, 3, 9, 5, 4), 33))
+    forced = (((64, 5, 50), 16), ((128, 3, 7, 9), 5), ((65, 4, 33), 70), ((127, 2, 100), 20), ((192, 7, 40), 8),
+              ((80, 6, 3), 3), ((1000, 3, 17), 9))
+    try:
+        for tune in ({}, {"pair_rows": 1}, {"pair_rows": 1, "row_blocks": 1}, {"pair_rows": 1, "row_blocks": 3, "max_steps": 4},
+                     {"pair_rows": 1, "max_col_blocks": 1}):
+            for key, val in tune.items():
+                mt.mttkrp_tune_set(key, val)
+            for dims, R in (picked if not tune else picked + forced):
+                k = 1
+                desc = mt.mttkrp_plan_describe(dims, R, k, sb)
+                print("paired rows %s dims=%s R=%d %s %s" % (tune, dims, R, dtype, desc), flush=True)
+                assert "paired_rows=1" in desc, desc
+                X, A = make_problem(dims, R, dtype, seed=91 + len(dims))
+                Xn = inputs.as_ndarray_view(X, dims)
+                An = [a.numpy() for a in A]
+                Xd = X.cuda()
+                Ad = [a.cuda() for a in A]
+                ref = oracle.mttkrp(Xn, An, k)
+                for _ in range(2):
+                    got = mt.mttkrp_dense(Xd, dims, Ad, k)
+                    torch.cuda.synchronize()
+                    assert oracle.normwise_rel_err(got.cpu().numpy(), ref) <= TOL[dtype], (dims, R, tune)
+                lam = inputs.uniform(99, R, 0.5, 1.5, dtype=dtype)
+                wide = []
+                for m, a in enumerate(A):
+                    buf = torch.full((dims[m], R + 1 + m), float("nan"), dtype=dtype, device="cuda")
+                    buf[:, :R] = Ad[m]
+                    wide.append(buf)
+                Mw = torch.full((dims[k], R + 3), 1.0, dtype=dtype, device="cuda")
+                mt.mttkrp_dense_ld(Xd, dims, [w[:, :R] for w in wide], k, Mw[:, :R], R, lam=lam.cuda(), beta=0.5)
+                torch.cuda.synchronize()
+                ref2 = oracle.mttkrp(Xn, An, k, lam=lam.numpy()) + 0.5
+                assert oracle.normwise_rel_err(Mw[:, :R].cpu().numpy(), ref2) <= TOL[dtype], (dims, R, tune)
+                assert bool((Mw[:, R:] == 1.0).all())
+            for key in tune:
+                mt.mttkrp_tune_set(key, 0)
+        # not for other modes, not with I_0 below one full tile, not when switched off
+        assert "paired_rows=0" in mt.mttkrp_plan_describe((401, 21, 12, 11), 32, 2, sb)
+        assert "paired_rows=0" in mt.mttkrp_plan_describe((400, 21, 12, 11), 32, 1, sb)
+        mt.mttkrp_tune_set("pair_rows", 1)
+        assert "paired_rows=0" in mt.mttkrp_plan_describe((63, 21, 12, 11), 32, 1, sb)
+        mt.mttkrp_tune_set("pair_rows", 2)
+        assert "paired_rows=0" in mt.mttkrp_plan_describe((401, 21, 12, 11), 32, 1, sb)
+    finally:
+        for key in TUNE_KEYS:
+            mt.mttkrp_tune_set(key, 0)
 
 
 def test_seeded_random_shapes(mt, oracle):
