@@ -74,8 +74,10 @@ int mttkrp_dense_all_modes_f32(int ndim, const int64_t* dims, const float* X,
  *   other arguments as mttkrp_dense_all_modes_*; M_out[k] may be one buffer for all k only
  *   if the caller consumes each result in stream order (the CP-ALS driver does).
  * Returns MTTKRP_ERR_UNSUPPORTED for a shape without a cut that fits, MTTKRP_ERR_WORKSPACE
- * for a workspace that is too small.  The core calls it makes use the library-owned
- * workspace of the stream.
+ * for a workspace that is too small.  Everything the call needs, the partial sums of the
+ * core call of its first pass included, lies in `workspace`: it only enqueues kernels
+ * (no allocation, no memset, no copy), so it may be recorded into a HIP graph.  The byte
+ * count depends on the decomposition parameters (mttkrp_tune_set) in force at the query.
  */
 size_t mttkrp_dense_all_modes_shared_bytes(int ndim, const int64_t* dims, int R, int dtype_bytes);
 int mttkrp_dense_all_modes_shared_f64(int ndim, const int64_t* dims, const double* X,

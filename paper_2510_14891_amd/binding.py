@@ -409,9 +409,11 @@ def mttkrp_dense_all_modes_shared_bytes(dims: Sequence[int], R: int, dtype_bytes
 
 
 def mttkrp_dense_all_modes_shared(X, dims: Sequence[int], factors: Sequence, M_out=None,
-                                  stream: Optional[int] = None):
+                                  stream: Optional[int] = None, workspace=None):
     """[M_0, ..., M_{d-1}] from two passes over X (partial contractions shared between the
-    modes); see mttkrp_dense_all_modes_shared_f64 in include/mttkrp_cpals.h."""
+    modes); see mttkrp_dense_all_modes_shared_f64 in include/mttkrp_cpals.h.  ``workspace``: an
+    optional torch tensor of at least mttkrp_dense_all_modes_shared_bytes(...) bytes on X's
+    device (default: a buffer this module keeps per stream)."""
     import torch
     L = lib()
     suffix, d, ptrs, R, M0, stream = _marshal(X, dims, factors, 0, None if M_out is None else M_out[0], stream)
@@ -429,7 +431,13 @@ def mttkrp_dense_all_modes_shared(X, dims: Sequence[int], factors: Sequence, M_o
     nbytes = mttkrp_dense_all_modes_shared_bytes(dims, R, X.element_size())
     if nbytes == 0:
         raise MttkrpError(MTTKRP_ERR_UNSUPPORTED, "no supported cut for this shape")
-    ws = _scratch(X.device, stream, nbytes)
+    if workspace is not None:
+        if workspace.device != X.device or not workspace.is_contiguous() \
+                or workspace.numel() * workspace.element_size() < nbytes:
+            raise ValueError("workspace must be a contiguous tensor of at least %d bytes on X's device" % nbytes)
+        ws = workspace
+    else:
+        ws = _scratch(X.device, stream, nbytes)
     with torch.cuda.device(X.device):
         rc = getattr(L, "mttkrp_dense_all_modes_shared_" + suffix)(
             d, _dims_array(dims), X.data_ptr(), ptrs, R, outs, ws.data_ptr(), nbytes, ctypes.c_void_p(stream))

@@ -561,14 +561,16 @@ sum_segments(const double* __restrict__ part, int64_t n_entries, int R, int n_se
 
 template <typename T> struct Calls;
 template <> struct Calls<double> {
-    static int dense(int nd, const int64_t* d, const double* X, const double* const* f, int R, int k, double* M, void* st)
-    { return mttkrp_dense_f64(nd, d, X, f, R, k, M, st); }
+    static int dense(int nd, const int64_t* d, const double* X, const double* const* f, int R, int k, double* M,
+                     void* ws, size_t wsb, void* st)
+    { return mttkrp_dense_f64_ws(nd, d, X, f, R, k, M, ws, wsb, st); }
     static int leading(int64_t P, int64_t Q, const double* X, const double* K, int R, double* out, void* ws, size_t wsb, void* st)
     { return mttkrp_contract_leading_f64(P, Q, X, K, R, R, out, R, ws, wsb, st); }
 };
 template <> struct Calls<float> {
-    static int dense(int nd, const int64_t* d, const float* X, const float* const* f, int R, int k, float* M, void* st)
-    { return mttkrp_dense_f32(nd, d, X, f, R, k, M, st); }
+    static int dense(int nd, const int64_t* d, const float* X, const float* const* f, int R, int k, float* M,
+                     void* ws, size_t wsb, void* st)
+    { return mttkrp_dense_f32_ws(nd, d, X, f, R, k, M, ws, wsb, st); }
     static int leading(int64_t P, int64_t Q, const float* X, const float* K, int R, float* out, void* ws, size_t wsb, void* st)
     { return mttkrp_contract_leading_f32(P, Q, X, K, R, R, out, R, ws, wsb, st); }
 };
@@ -580,6 +582,10 @@ struct SharedPlan {
     int64_t PL = 1, PR = 1;
     int max_seg = 1;
     size_t off_TR = 0, off_KL = 0, off_TL = 0, off_part = 0, off_lead = 0, lead_bytes = 0, total = 0;
+    // the first pass is a first-mode core call on (P_L, I_s, ..., I_{d-1}); its workspace
+    int nd_first = 0;
+    int64_t dims_first[MTTKRP_MAX_NDIM];
+    size_t off_first = 0, first_bytes = 0;
 };
 
 size_t align256(size_t n) { return (n + 255) / 256 * 256; }
@@ -657,6 +663,15 @@ int plan_shared(int ndim, const int64_t* dims, int R, int sbytes, SharedPlan& sp
         return MTTKRP_ERR_UNSUPPORTED;
     sp.lead_bytes = lead;
     sp.off_lead = off;  off += align256(lead);
+    sp.nd_first = 1 + ndim - sp.s;
+    sp.dims_first[0] = sp.PL;
+    for (int m = sp.s; m < ndim; ++m)
+        sp.dims_first[1 + m - sp.s] = dims[m];
+    const size_t first = mttkrp_dense_workspace_bytes(sp.nd_first, sp.dims_first, R, 0, sbytes);
+    if (first == (size_t)-1)
+        return MTTKRP_ERR_UNSUPPORTED;
+    sp.first_bytes = first;
+    sp.off_first = off;  off += align256(first);
     sp.total = off > 0 ? off : 256;
     // the intermediates must stay small beside the tensor: an eighth of it, or 64 MiB
     double limit = 0.125 * (double)N * sbytes;
@@ -729,23 +744,19 @@ int shared_sweep(int ndim, const int64_t* dims, const T* X, const T* const* fact
     const int s = sp.s, nr = ndim - s;
     // pass 1: contraction over the trailing modes
     if (s == 1) {
-        rc = Calls<T>::dense(ndim, dims, X, factors, R, 0, M_out[0], stream);
+        rc = Calls<T>::dense(ndim, dims, X, factors, R, 0, M_out[0], ws + sp.off_first, sp.first_bytes, stream);
         if (rc != MTTKRP_OK)
             return rc;
         rc = after(0);
         if (rc != MTTKRP_OK)
             return rc;
     } else {
-        int64_t d2[MTTKRP_MAX_NDIM];
         const T* f2[MTTKRP_MAX_NDIM];
-        d2[0] = sp.PL;
         f2[0] = nullptr;
-        for (int m = 0; m < nr; ++m) {
-            d2[1 + m] = dims[s + m];
+        for (int m = 0; m < nr; ++m)
             f2[1 + m] = factors[s + m];
-        }
         T* const TR = (T*)(ws + sp.off_TR);
-        rc = Calls<T>::dense(1 + nr, d2, X, f2, R, 0, TR, stream);
+        rc = Calls<T>::dense(sp.nd_first, sp.dims_first, X, f2, R, 0, TR, ws + sp.off_first, sp.first_bytes, stream);
         if (rc != MTTKRP_OK)
             return rc;
         for (int k = 0; k < s; ++k) {
