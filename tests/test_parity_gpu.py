@@ -31,7 +31,7 @@ def mt():
 
 
 TUNE_KEYS = ("row_blocks", "target_items", "max_steps", "xcd_remap", "ws_percent",
-             "max_col_blocks", "first_group", "deep", "waves_per_simd", "nt_loads", "fuse_bytes", "inner_splits", "contract_rows", "rows_col_blocks", "linear", "pair_rows")
+             "max_col_blocks", "first_group", "deep", "waves_per_simd", "nt_loads", "fuse_bytes", "inner_splits", "contract_rows", "rows_col_blocks", "linear", "pair_rows", "fuse_rows")
 
 
 def make_problem(dims, R, dtype, seed, dist=("uniform", -1.0, 1.0)):
@@ -241,6 +241,8 @@ def test_result_does_not_depend_on_the_decomposition(mt, oracle, dtype):
         {"fuse_bytes": 1}, {"inner_splits": 1}, {"inner_splits": 5}, {"fuse_bytes": 1 << 30}, {"fuse_bytes": 1 << 30, "target_items": 64},
         {"linear": 1}, {"linear": 1, "target_items": 777}, {"linear": 1, "first_group": 1, "target_items": 100000},
         {"linear": 1, "deep": 2, "max_steps": 5}, {"linear": 2, "first_group": 1},
+        {"pair_rows": 1}, {"pair_rows": 2}, {"pair_rows": 1, "row_blocks": 2, "target_items": 50000},
+        {"fuse_rows": 1}, {"fuse_rows": 2}, {"fuse_rows": 1, "fuse_bytes": 1 << 30, "max_steps": 6},
     ]
     try:
         for st in settings:
@@ -504,13 +506,15 @@ def test_fused_row_modes(mt, oracle, dtype):
 @pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
 def test_paired_rows_for_mode_1(mt, oracle, dtype):
     """k = 1 with the pairs (i_0, i_1) taken as the rows and each tile's rows summed per value of
-    i_1: shapes the planner picks it for (I_0 not near a multiple of the row tiles), and forced on
+    i_1: shapes the planner picks it for (I_0 not near a multiple of the row tiles, or so short
+    that a wavefront would hold one or two row blocks), and forced on
     for extents where the ranges of i_0 begin on tile boundaries (64, 128), just off them (65, 127),
     with few and many column entries (one split and many), tiles of 16 to 64 rows, ragged R, one
     and several chunks of output columns; plain call, leading dimensions with NaN padding, lambda
     and beta, and twice in a row in one workspace (unwritten slots are cleared at every call)."""
     sb = 8 if dtype == torch.float64 else 4
-    picked = (((401, 21, 12, 11), 32), ((129, 9, 40, 7), 10), ((100, 5, 300), 7), ((70, 3, 9, 5, 4), 33))
+    picked = (((401, 21, 12, 11), 32), ((129, 9, 40, 7), 10), ((100, 5, 300), 7), ((70, 3, 9, 5, 4), 33),
+              ((80, 6, 30, 7), 12), ((400, 5, 9, 11), 20))
     forced = (((64, 5, 50), 16), ((128, 3, 7, 9), 5), ((65, 4, 33), 70), ((127, 2, 100), 20), ((192, 7, 40), 8),
               ((80, 6, 3), 3), ((1000, 3, 17), 9))
     try:
@@ -549,7 +553,7 @@ def test_paired_rows_for_mode_1(mt, oracle, dtype):
                 mt.mttkrp_tune_set(key, 0)
         # not for other modes, not with I_0 below one full tile, not when switched off
         assert "paired_rows=0" in mt.mttkrp_plan_describe((401, 21, 12, 11), 32, 2, sb)
-        assert "paired_rows=0" in mt.mttkrp_plan_describe((400, 21, 12, 11), 32, 1, sb)
+        assert "paired_rows=0" in mt.mttkrp_plan_describe((192, 21, 12, 11), 32, 1, sb)
         mt.mttkrp_tune_set("pair_rows", 1)
         assert "paired_rows=0" in mt.mttkrp_plan_describe((63, 21, 12, 11), 32, 1, sb)
         mt.mttkrp_tune_set("pair_rows", 2)
