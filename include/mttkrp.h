@@ -273,14 +273,18 @@ int mttkrp_timing_last(float* stream_ms, float* combine_ms);
  *   "nt_loads"      1 = never use non-temporal tensor loads, 0 = chosen by alignment
  *   "fuse_bytes"    largest product matrix (bytes) for which two adjacent modes
  *                   are fused into one (default 8 MiB; 1 = never fuse)
- *   "pair_rows"     k = 1 only: 1 = take the pairs (i_0, i_1) as the rows whenever I_0 >= 64
- *                   (no padded row blocks; the epilogue sums each tile per i_1), 2 = never,
- *                   0 = when I_0 alone leaves more than 1 % of the tiles' rows empty or allows
- *                   only one or two row blocks per wavefront
+ *   "pair_rows"     k = 1, and k = 0 with I_0 <= 32: 1 = take the pairs (i_0, i_1) as the rows
+ *                   (no padded row blocks; the epilogue sums each tile per output row), 2 =
+ *                   never, 0 = when I_0 alone leaves more than 1 % of the tiles' rows empty or
+ *                   allows only one or two row blocks per wavefront
  *   "fuse_rows"     k >= 2 only: 1 = modes 0 and 1 are one row mode (their factors' row-wise
  *                   product as its factor) whenever that product stays within four times
  *                   "fuse_bytes", 2 = never, 0 = by the same rule as "pair_rows" when the sweeps
  *                   that remain stay long
+ *   "lead_last"     last mode only: 1 = as one contraction over all other modes (X^T times the
+ *                   Khatri-Rao product of their factors, formed in the workspace) whenever that
+ *                   product stays below 4 MiB, 2 = never, 0 = then and when mode 0 fills the row
+ *                   tiles badly, I_k >= 256 and no large partial sums are needed
  *   "contract_rows" schedule for k != 0: 1 = contract over mode 0 (rows) whenever the
  *                   other modes' entries number at most 1024, 2 = never, 0 = chosen by
  *                   the planner (those entries few, under 128, mode 0 at least eight

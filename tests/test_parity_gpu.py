@@ -31,7 +31,7 @@ def mt():
 
 
 TUNE_KEYS = ("row_blocks", "target_items", "max_steps", "xcd_remap", "ws_percent",
-             "max_col_blocks", "first_group", "deep", "waves_per_simd", "nt_loads", "fuse_bytes", "inner_splits", "contract_rows", "rows_col_blocks", "linear", "pair_rows", "fuse_rows")
+             "max_col_blocks", "first_group", "deep", "waves_per_simd", "nt_loads", "fuse_bytes", "inner_splits", "contract_rows", "rows_col_blocks", "linear", "pair_rows", "fuse_rows", "lead_last")
 
 
 def make_problem(dims, R, dtype, seed, dist=("uniform", -1.0, 1.0)):
@@ -243,6 +243,7 @@ def test_result_does_not_depend_on_the_decomposition(mt, oracle, dtype):
         {"linear": 1, "deep": 2, "max_steps": 5}, {"linear": 2, "first_group": 1},
         {"pair_rows": 1}, {"pair_rows": 2}, {"pair_rows": 1, "row_blocks": 2, "target_items": 50000},
         {"fuse_rows": 1}, {"fuse_rows": 2}, {"fuse_rows": 1, "fuse_bytes": 1 << 30, "max_steps": 6},
+        {"lead_last": 1}, {"lead_last": 2}, {"lead_last": 1, "max_steps": 2, "rows_col_blocks": 1},
     ]
     try:
         for st in settings:
@@ -504,29 +505,34 @@ def test_fused_row_modes(mt, oracle, dtype):
 
 
 @pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
-def test_paired_rows_for_mode_1(mt, oracle, dtype):
-    """k = 1 with the pairs (i_0, i_1) taken as the rows and each tile's rows summed per value of
-    i_1: shapes the planner picks it for (I_0 not near a multiple of the row tiles, or so short
-    that a wavefront would hold one or two row blocks), and forced on
-    for extents where the ranges of i_0 begin on tile boundaries (64, 128), just off them (65, 127),
-    with few and many column entries (one split and many), tiles of 16 to 64 rows, ragged R, one
-    and several chunks of output columns; plain call, leading dimensions with NaN padding, lambda
-    and beta, and twice in a row in one workspace (unwritten slots are cleared at every call)."""
+def test_paired_rows_for_the_first_two_modes(mt, oracle, dtype):
+    """k = 1 (and k = 0 with a short first mode) with the pairs (i_0, i_1) taken as the rows and
+    each tile's rows summed per output row: shapes the planner picks it for (I_0 not near a
+    multiple of the row tiles, or so short that a wavefront would hold one or two row blocks; I_0
+    from 1 to 401, so that a tile meets from one to 64 output rows), and forced on for extents
+    where the ranges of i_0 begin on tile boundaries (64, 128), just off them (65, 127), with few
+    and many column entries (one split and many), tiles of 16 to 64 rows, ragged R, one and
+    several chunks of output columns; plain call, leading dimensions with NaN padding, lambda and
+    beta, and twice in a row in one workspace (unwritten slots are cleared at every call)."""
     sb = 8 if dtype == torch.float64 else 4
-    picked = (((401, 21, 12, 11), 32), ((129, 9, 40, 7), 10), ((100, 5, 300), 7), ((70, 3, 9, 5, 4), 33),
-              ((80, 6, 30, 7), 12), ((400, 5, 9, 11), 20))
-    forced = (((64, 5, 50), 16), ((128, 3, 7, 9), 5), ((65, 4, 33), 70), ((127, 2, 100), 20), ((192, 7, 40), 8),
-              ((80, 6, 3), 3), ((1000, 3, 17), 9))
+    picked = (((401, 21, 12, 11), 32, 1), ((129, 9, 40, 7), 10, 1), ((100, 5, 300), 7, 1), ((70, 3, 9, 5, 4), 33, 1),
+              ((80, 6, 30, 7), 12, 1), ((400, 5, 9, 11), 20, 1),
+              ((3, 50, 40, 7), 16, 1), ((10, 33, 20, 9), 40, 1), ((20, 30, 40, 5), 8, 1), ((2, 100, 300), 5, 1),
+              ((31, 7, 50), 17, 1), ((1, 40, 90), 6, 1), ((7, 9, 11, 13, 5), 70, 1), ((17, 200, 33), 24, 1),
+              ((3, 50, 40, 7), 16, 0), ((10, 33, 20, 9), 40, 0), ((20, 30, 40, 5), 8, 0), ((2, 100, 300), 5, 0),
+              ((31, 7, 50), 17, 0), ((1, 40, 90), 6, 0), ((7, 9, 11, 13, 5), 70, 0), ((17, 200, 33), 24, 0),
+              ((32, 3, 500), 33, 0), ((5, 2000, 9), 3, 0))
+    forced = (((64, 5, 50), 16, 1), ((128, 3, 7, 9), 5, 1), ((65, 4, 33), 70, 1), ((127, 2, 100), 20, 1), ((192, 7, 40), 8, 1),
+              ((80, 6, 3), 3, 1), ((1000, 3, 17), 9, 1), ((16, 16, 50), 16, 0), ((16, 16, 50), 16, 1), ((32, 8, 70), 20, 0))
     try:
         for tune in ({}, {"pair_rows": 1}, {"pair_rows": 1, "row_blocks": 1}, {"pair_rows": 1, "row_blocks": 3, "max_steps": 4},
                      {"pair_rows": 1, "max_col_blocks": 1}):
             for key, val in tune.items():
                 mt.mttkrp_tune_set(key, val)
-            for dims, R in (picked if not tune else picked + forced):
-                k = 1
+            for dims, R, k in (picked if not tune else picked + forced):
                 desc = mt.mttkrp_plan_describe(dims, R, k, sb)
-                print("paired rows %s dims=%s R=%d %s %s" % (tune, dims, R, dtype, desc), flush=True)
-                assert "paired_rows=1" in desc, desc
+                print("paired rows %s dims=%s R=%d k=%d %s %s" % (tune, dims, R, k, dtype, desc), flush=True)
+                assert ("paired_rows=1" if k == 1 else "paired_rows=2") in desc, desc
                 X, A = make_problem(dims, R, dtype, seed=91 + len(dims))
                 Xn = inputs.as_ndarray_view(X, dims)
                 An = [a.numpy() for a in A]
@@ -534,10 +540,74 @@ def test_paired_rows_for_mode_1(mt, oracle, dtype):
                 Ad = [a.cuda() for a in A]
                 ref = oracle.mttkrp(Xn, An, k)
                 for _ in range(2):
-                    got = mt.mttkrp_dense(Xd, dims, Ad, k)
+                    got = mt.mttkrp_dense(Xd, dims, [None if m == k else a for m, a in enumerate(Ad)], k)
                     torch.cuda.synchronize()
-                    assert oracle.normwise_rel_err(got.cpu().numpy(), ref) <= TOL[dtype], (dims, R, tune)
+                    assert oracle.normwise_rel_err(got.cpu().numpy(), ref) <= TOL[dtype], (dims, R, k, tune)
                 lam = inputs.uniform(99, R, 0.5, 1.5, dtype=dtype)
+                wide = []
+                for m, a in enumerate(A):
+                    buf = torch.full((dims[m], R + 1 + m), float("nan"), dtype=dtype, device="cuda")
+                    buf[:, :R] = Ad[m]
+                    wide.append(buf)
+                Mw = torch.full((dims[k], R + 3), 1.0, dtype=dtype, device="cuda")
+                mt.mttkrp_dense_ld(Xd, dims, [w[:, :R] for w in wide], k, Mw[:, :R], R, lam=lam.cuda(), beta=0.5)
+                torch.cuda.synchronize()
+                ref2 = oracle.mttkrp(Xn, An, k, lam=lam.numpy()) + 0.5
+                assert oracle.normwise_rel_err(Mw[:, :R].cpu().numpy(), ref2) <= TOL[dtype], (dims, R, k, tune)
+                assert bool((Mw[:, R:] == 1.0).all())
+            for key in tune:
+                mt.mttkrp_tune_set(key, 0)
+        # not for other modes, not for a first mode of more than 32 entries, not for matrices, not
+        # where I_0 fills its tiles, not when switched off
+        assert "paired_rows=0" in mt.mttkrp_plan_describe((401, 21, 12, 11), 32, 2, sb)
+        assert "paired_rows=0" in mt.mttkrp_plan_describe((192, 21, 12, 11), 32, 1, sb)
+        assert "paired_rows=0" in mt.mttkrp_plan_describe((33, 21, 12, 11), 32, 0, sb)
+        assert "paired_rows=0" in mt.mttkrp_plan_describe((20, 500), 8, 0, sb)
+        assert "paired_rows=0" in mt.mttkrp_plan_describe((20, 500), 8, 1, sb)
+        mt.mttkrp_tune_set("pair_rows", 2)
+        assert "paired_rows=0" in mt.mttkrp_plan_describe((401, 21, 12, 11), 32, 1, sb)
+        assert "paired_rows=0" in mt.mttkrp_plan_describe((3, 50, 40, 7), 16, 0, sb)
+    finally:
+        for key in TUNE_KEYS:
+            mt.mttkrp_tune_set(key, 0)
+
+
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+def test_last_mode_as_contraction_over_all_other_modes(mt, oracle, dtype):
+    """The last mode when all other modes together are short: M = X^T K with K the Khatri-Rao
+    product of the other factors, formed in the workspace by a chain of pairwise products (none
+    for a matrix, one for three modes, three for five).  Shapes the planner picks it for and
+    shapes it is forced on (row splits with partial sums, one and several column chunks of R,
+    ragged extents); plain call without the k-th factor, leading dimensions with NaN padding,
+    lambda and beta with and without row splits."""
+    sb = 8 if dtype == torch.float64 else 4
+    picked = (((20, 20, 5000), 8), ((10, 13, 700), 70), ((20, 500), 8), ((2, 3, 40000), 5), ((7, 5, 3, 150000), 12))
+    forced = (((64, 64, 300), 16), ((100, 30, 400), 24), ((17, 3, 2, 2, 2, 90), 33), ((300, 5, 20), 130),
+              ((20, 20, 5000), 32), ((3, 4, 5, 6, 700), 10), ((5, 7, 9, 1000), 16))
+    try:
+        for tune in ({}, {"lead_last": 1}, {"lead_last": 1, "max_steps": 2}, {"lead_last": 1, "max_col_blocks": 1, "target_items": 50000}):
+            for key, val in tune.items():
+                mt.mttkrp_tune_set(key, val)
+            for dims, R in (picked if not tune else picked + forced):
+                k = len(dims) - 1
+                desc = mt.mttkrp_plan_describe(dims, R, k, sb)
+                print("last mode %s dims=%s R=%d %s %s" % (tune, dims, R, dtype, desc), flush=True)
+                assert "shape=leading" in desc, desc
+                X, A = make_problem(dims, R, dtype, seed=57 + len(dims))
+                Xn = inputs.as_ndarray_view(X, dims)
+                An = [a.numpy() for a in A]
+                Xd = X.cuda()
+                Ad = [a.cuda() for a in A]
+                ref = oracle.mttkrp(Xn, An, k)
+                got = mt.mttkrp_dense(Xd, dims, Ad[:k] + [None], k)
+                torch.cuda.synchronize()
+                assert oracle.normwise_rel_err(got.cpu().numpy(), ref) <= TOL[dtype], (dims, R, tune)
+                ws = torch.empty(max(1, mt.mttkrp_dense_workspace_bytes(dims, R, k, sb)), dtype=torch.uint8, device="cuda")
+                ws.fill_(255)
+                got = mt.mttkrp_dense(Xd, dims, Ad, k, workspace=ws)
+                torch.cuda.synchronize()
+                assert oracle.normwise_rel_err(got.cpu().numpy(), ref) <= TOL[dtype], (dims, R, tune)
+                lam = inputs.uniform(96, R, 0.5, 1.5, dtype=dtype)
                 wide = []
                 for m, a in enumerate(A):
                     buf = torch.full((dims[m], R + 1 + m), float("nan"), dtype=dtype, device="cuda")
@@ -551,13 +621,13 @@ def test_paired_rows_for_mode_1(mt, oracle, dtype):
                 assert bool((Mw[:, R:] == 1.0).all())
             for key in tune:
                 mt.mttkrp_tune_set(key, 0)
-        # not for other modes, not with I_0 below one full tile, not when switched off
-        assert "paired_rows=0" in mt.mttkrp_plan_describe((401, 21, 12, 11), 32, 2, sb)
-        assert "paired_rows=0" in mt.mttkrp_plan_describe((192, 21, 12, 11), 32, 1, sb)
-        mt.mttkrp_tune_set("pair_rows", 1)
-        assert "paired_rows=0" in mt.mttkrp_plan_describe((63, 21, 12, 11), 32, 1, sb)
-        mt.mttkrp_tune_set("pair_rows", 2)
-        assert "paired_rows=0" in mt.mttkrp_plan_describe((401, 21, 12, 11), 32, 1, sb)
+        # not for other modes, not where mode 0 fills its row tiles, not with many entries in the
+        # other modes, not when switched off
+        assert "shape=leading" not in mt.mttkrp_plan_describe((20, 20, 5000), 8, 1, sb)
+        assert "shape=leading" not in mt.mttkrp_plan_describe((64, 64, 5000), 8, 2, sb)
+        assert "shape=leading" not in mt.mttkrp_plan_describe((20, 2000, 5000), 64, 2, sb)
+        mt.mttkrp_tune_set("lead_last", 2)
+        assert "shape=leading" not in mt.mttkrp_plan_describe((20, 20, 5000), 8, 2, sb)
     finally:
         for key in TUNE_KEYS:
             mt.mttkrp_tune_set(key, 0)
