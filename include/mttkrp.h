@@ -273,8 +273,9 @@ int mttkrp_timing_last(float* stream_ms, float* combine_ms);
  *   "nt_loads"      1 = never use non-temporal tensor loads, 0 = chosen by alignment
  *   "fuse_bytes"    largest product matrix (bytes) for which two adjacent modes
  *                   are fused into one (default 8 MiB; 1 = never fuse)
- *   "pair_rows"     k = 1, and k = 0 with I_0 <= 32: 1 = take the pairs (i_0, i_1) as the rows
- *                   (no padded row blocks; the epilogue sums each tile per output row), 2 =
+ *   "pair_rows"     k = 0 and k = 1: 1 = take the pairs (i_0, i_1) as the rows (no padded row
+ *                   blocks; the epilogue sums each tile per output row, or, for k = 0 with
+ *                   I_0 > 32, stores the weighted tile for the combine kernel), 2 =
  *                   never, 0 = when I_0 alone leaves more than 1 % of the tiles' rows empty or
  *                   allows only one or two row blocks per wavefront
  *   "fuse_rows"     k >= 2 only: 1 = modes 0 and 1 are one row mode (their factors' row-wise

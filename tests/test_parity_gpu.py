@@ -506,8 +506,9 @@ def test_fused_row_modes(mt, oracle, dtype):
 
 @pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
 def test_paired_rows_for_the_first_two_modes(mt, oracle, dtype):
-    """k = 1 (and k = 0 with a short first mode) with the pairs (i_0, i_1) taken as the rows and
-    each tile's rows summed per output row: shapes the planner picks it for (I_0 not near a
+    """k = 1 and k = 0 with the pairs (i_0, i_1) taken as the rows and each tile's rows summed per
+    output row (k = 0 with more than 32 rows: the weighted tiles stored whole and summed by the
+    combine kernel): shapes the planner picks it for (I_0 not near a
     multiple of the row tiles, or so short that a wavefront would hold one or two row blocks; I_0
     from 1 to 401, so that a tile meets from one to 64 output rows), and forced on for extents
     where the ranges of i_0 begin on tile boundaries (64, 128), just off them (65, 127), with few
@@ -523,7 +524,10 @@ def test_paired_rows_for_the_first_two_modes(mt, oracle, dtype):
               ((31, 7, 50), 17, 0), ((1, 40, 90), 6, 0), ((7, 9, 11, 13, 5), 70, 0), ((17, 200, 33), 24, 0),
               ((32, 3, 500), 33, 0), ((5, 2000, 9), 3, 0))
     forced = (((64, 5, 50), 16, 1), ((128, 3, 7, 9), 5, 1), ((65, 4, 33), 70, 1), ((127, 2, 100), 20, 1), ((192, 7, 40), 8, 1),
-              ((80, 6, 3), 3, 1), ((1000, 3, 17), 9, 1), ((16, 16, 50), 16, 0), ((16, 16, 50), 16, 1), ((32, 8, 70), 20, 0))
+              ((80, 6, 3), 3, 1), ((1000, 3, 17), 9, 1), ((16, 16, 50), 16, 0), ((16, 16, 50), 16, 1), ((32, 8, 70), 20, 0),
+              # first mode of more than 32 entries: the weighted tiles are stored whole
+              ((40, 30, 20, 9), 16, 0), ((129, 9, 40, 7), 10, 0), ((50, 7, 300), 33, 0), ((100, 5, 9, 11), 70, 0),
+              ((64, 5, 50), 16, 0), ((401, 21, 12, 11), 32, 0), ((33, 2, 500), 5, 0))
     try:
         for tune in ({}, {"pair_rows": 1}, {"pair_rows": 1, "row_blocks": 1}, {"pair_rows": 1, "row_blocks": 3, "max_steps": 4},
                      {"pair_rows": 1, "max_col_blocks": 1}):
@@ -532,7 +536,7 @@ def test_paired_rows_for_the_first_two_modes(mt, oracle, dtype):
             for dims, R, k in (picked if not tune else picked + forced):
                 desc = mt.mttkrp_plan_describe(dims, R, k, sb)
                 print("paired rows %s dims=%s R=%d k=%d %s %s" % (tune, dims, R, k, dtype, desc), flush=True)
-                assert ("paired_rows=1" if k == 1 else "paired_rows=2") in desc, desc
+                assert ("paired_rows=1" if k == 1 else ("paired_rows=2" if dims[0] <= 32 else "paired_rows=3")) in desc, desc
                 X, A = make_problem(dims, R, dtype, seed=91 + len(dims))
                 Xn = inputs.as_ndarray_view(X, dims)
                 An = [a.numpy() for a in A]
@@ -557,11 +561,11 @@ def test_paired_rows_for_the_first_two_modes(mt, oracle, dtype):
                 assert bool((Mw[:, R:] == 1.0).all())
             for key in tune:
                 mt.mttkrp_tune_set(key, 0)
-        # not for other modes, not for a first mode of more than 32 entries, not for matrices, not
-        # where I_0 fills its tiles, not when switched off
+        # not for other modes, not for a first mode of 64-row tiles that are 89 % full, not for
+        # matrices, not where I_0 fills its tiles, not when switched off
         assert "paired_rows=0" in mt.mttkrp_plan_describe((401, 21, 12, 11), 32, 2, sb)
         assert "paired_rows=0" in mt.mttkrp_plan_describe((192, 21, 12, 11), 32, 1, sb)
-        assert "paired_rows=0" in mt.mttkrp_plan_describe((33, 21, 12, 11), 32, 0, sb)
+        assert "paired_rows=0" in mt.mttkrp_plan_describe((401, 201, 12, 501), 32, 0, sb)
         assert "paired_rows=0" in mt.mttkrp_plan_describe((20, 500), 8, 0, sb)
         assert "paired_rows=0" in mt.mttkrp_plan_describe((20, 500), 8, 1, sb)
         mt.mttkrp_tune_set("pair_rows", 2)
