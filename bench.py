@@ -352,7 +352,8 @@ def time_shape(args) -> int:
         mt.mttkrp_timing_enable(False)
         desc = dict(t.split("=") for t in mt.mttkrp_plan_describe(dims, R, k, sb).split())
         rows = ("%s x %s" % (desc.get("rows_per_wave"), desc.get("row_blocks"))
-                if "rows_per_wave" in desc else "second schedule")
+                if "rows_per_wave" in desc else
+                ("last mode over all others" if desc.get("shape") == "leading" else "second schedule"))
         print("| %s | %d | %s | %d | %.3f + %.3f | %.0f | %.1f | %.3f | %s | %s x %s |" % (
             "x".join(str(d) for d in dims), R, args.dtype, k + 1, tm, tc, n * sb / (tm + tc) / 1e6,
             2.0 * n * R / (tm + tc) / 1e9, floor / tm, rows, desc.get("items"), desc.get("steps_per_item")))
