@@ -285,7 +285,7 @@ int mttkrp_timing_last(float* stream_ms, float* combine_ms);
  *   "lead_last"     last mode only: 1 = as one contraction over all other modes (X^T times the
  *                   Khatri-Rao product of their factors, formed in the workspace) whenever that
  *                   product stays below 4 MiB, 2 = never, 0 = then and when mode 0 fills the row
- *                   tiles badly, I_k >= 256 and no large partial sums are needed
+ *                   tiles badly, I_k >= 256 and the rows need no splitting
  *   "contract_rows" schedule for k != 0: 1 = contract over mode 0 (rows) whenever the
  *                   other modes' entries number at most 1024, 2 = never, 0 = chosen by
  *                   the planner (those entries few, under 128, mode 0 at least eight

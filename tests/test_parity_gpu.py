@@ -585,8 +585,8 @@ def test_last_mode_as_contraction_over_all_other_modes(mt, oracle, dtype):
     ragged extents); plain call without the k-th factor, leading dimensions with NaN padding,
     lambda and beta with and without row splits."""
     sb = 8 if dtype == torch.float64 else 4
-    picked = (((20, 20, 5000), 8), ((10, 13, 700), 70), ((20, 500), 8), ((2, 3, 40000), 5), ((7, 5, 3, 150000), 12))
-    forced = (((64, 64, 300), 16), ((100, 30, 400), 24), ((17, 3, 2, 2, 2, 90), 33), ((300, 5, 20), 130),
+    picked = (((10, 13, 700), 70), ((20, 500), 8), ((2, 3, 40000), 5), ((7, 5, 3, 150000), 12))
+    forced = (((20, 20, 5000), 8), ((64, 64, 300), 16), ((100, 30, 400), 24), ((17, 3, 2, 2, 2, 90), 33), ((300, 5, 20), 130),
               ((20, 20, 5000), 32), ((3, 4, 5, 6, 700), 10), ((5, 7, 9, 1000), 16))
     try:
         for tune in ({}, {"lead_last": 1}, {"lead_last": 1, "max_steps": 2}, {"lead_last": 1, "max_col_blocks": 1, "target_items": 50000}):
@@ -627,11 +627,11 @@ def test_last_mode_as_contraction_over_all_other_modes(mt, oracle, dtype):
                 mt.mttkrp_tune_set(key, 0)
         # not for other modes, not where mode 0 fills its row tiles, not with many entries in the
         # other modes, not when switched off
-        assert "shape=leading" not in mt.mttkrp_plan_describe((20, 20, 5000), 8, 1, sb)
+        assert "shape=leading" not in mt.mttkrp_plan_describe((7, 5, 3, 150000), 12, 1, sb)
         assert "shape=leading" not in mt.mttkrp_plan_describe((64, 64, 5000), 8, 2, sb)
         assert "shape=leading" not in mt.mttkrp_plan_describe((20, 2000, 5000), 64, 2, sb)
         mt.mttkrp_tune_set("lead_last", 2)
-        assert "shape=leading" not in mt.mttkrp_plan_describe((20, 20, 5000), 8, 2, sb)
+        assert "shape=leading" not in mt.mttkrp_plan_describe((7, 5, 3, 150000), 12, 3, sb)
     finally:
         for key in TUNE_KEYS:
             mt.mttkrp_tune_set(key, 0)
