@@ -7,6 +7,8 @@ with the normwise relative error ||M_gpu - M_orc||_F / ||M_orc||_F:
 Eq. (elem) is a correct result, so parity is by norm, not by bits; what must be
 bit-identical is a rerun of the same call (fixed-order combine, no atomics).
 """
+import re
+
 import numpy as np
 import pytest
 
@@ -710,6 +712,58 @@ def test_seeded_random_shapes_long_first_mode(mt, oracle):
                 assert err <= TOL[dtype], (case, dims, R, k, tune, err)
             for key in tune:
                 mt.mttkrp_tune_set(key, 0)
+    finally:
+        for key in TUNE_KEYS:
+            mt.mttkrp_tune_set(key, 0)
+
+
+def test_seeded_random_shapes_short_leading_modes(mt, oracle):
+    """Two hundred seeded random problems with a short or ragged first mode (1 to 129 entries) and
+    other modes of up to 300, under planner settings that force or forbid the routes made for them:
+    the pairs (i_0, i_1) as rows for the first two modes (summed per output row, or stored whole),
+    fused rows for later modes, the last mode as a contraction over all other modes, many inner
+    splits, and the folded combine.  The tolerance is the one of the other tests, widened only for
+    ill-conditioned outputs (8 u c with c = ||MTTKRP of absolute values|| / ||MTTKRP||, the
+    forward-error bound of any summation order)."""
+    rng = np.random.default_rng(20240623)
+    I0s = (1, 2, 3, 5, 7, 10, 16, 17, 20, 31, 32, 33, 40, 50, 63, 64, 65, 100, 129)
+    Is = (1, 2, 3, 4, 5, 7, 9, 12, 16, 17, 33, 40, 64, 100, 300)
+    Rs = (1, 2, 3, 8, 10, 16, 17, 32, 33, 49, 64, 70, 130)
+    tunes = ({}, {}, {}, {"pair_rows": 1}, {"pair_rows": 1}, {"pair_rows": 2}, {"pair_rows": 1, "row_blocks": 2},
+             {"pair_rows": 1, "target_items": 50000}, {"pair_rows": 1, "max_steps": 3}, {"fuse_rows": 1},
+             {"fuse_rows": 1, "fuse_bytes": 1 << 30}, {"fuse_rows": 2, "pair_rows": 2}, {"lead_last": 1},
+             {"lead_last": 1, "max_steps": 2}, {"lead_last": 2}, {"target_items": 100000}, {"max_col_blocks": 1})
+    unit = {torch.float64: 2.0 ** -53, torch.float32: 2.0 ** -24}
+    seen = set()
+    try:
+        for case in range(200):
+            d = int(rng.choice((3, 3, 3, 4, 4, 5, 6, 7)))
+            dims = [int(rng.choice(I0s))] + [int(rng.choice(Is)) for _ in range(d - 1)]
+            while int(np.prod(dims)) > 400_000:
+                i = 1 + int(np.argmax(dims[1:]))
+                dims[i] = max(1, dims[i] // 2)
+            R = int(rng.choice(Rs))
+            dtype = torch.float64 if rng.random() < 0.6 else torch.float32
+            tune = tunes[int(rng.integers(len(tunes)))]
+            X, A = make_problem(tuple(dims), R, dtype, seed=12000 + case)
+            Xd, Ad = X.cuda(), [a.cuda() for a in A]
+            Xn, An = inputs.as_ndarray_view(X, dims), [a.numpy() for a in A]
+            for key in TUNE_KEYS:
+                mt.mttkrp_tune_set(key, tune.get(key, 0))
+            for k in range(d):
+                desc = mt.mttkrp_plan_describe(dims, R, k, X.element_size())
+                print("random short case %d dims=%s R=%d %s k=%d tune=%s %s" % (case, dims, R, dtype, k, tune, desc), flush=True)
+                seen.add(re.search(r"paired_rows=(\d)", desc).group(1) if "paired_rows=" in desc else "-")
+                seen.add("leading" if "shape=leading" in desc else ("fused" if "fused_rows=1" in desc else "plain"))
+                ref = oracle.mttkrp(Xn, An, k)
+                M = mt.mttkrp_dense(Xd, dims, Ad, k)
+                torch.cuda.synchronize()
+                err = oracle.normwise_rel_err(M.cpu().numpy(), ref)
+                if not err <= TOL[dtype]:
+                    c = np.linalg.norm(oracle.mttkrp(np.abs(Xn), [np.abs(a) for a in An], k)) / max(np.linalg.norm(ref), 1e-300)
+                    assert err <= 8.0 * unit[dtype] * c, (case, dims, R, k, tune, err, c)
+        # the sweep reached every route
+        assert {"1", "2", "3", "leading", "fused", "plain"} <= seen, seen
     finally:
         for key in TUNE_KEYS:
             mt.mttkrp_tune_set(key, 0)
