@@ -289,7 +289,8 @@ int mttkrp_timing_last(float* stream_ms, float* combine_ms);
  *   "contract_rows" schedule for k != 0: 1 = contract over mode 0 (rows) whenever the
  *                   other modes' entries number at most 1024, 2 = never, 0 = chosen by
  *                   the planner (those entries few, under 128, mode 0 at least eight
- *                   times as long, and R large enough for the data type)
+ *                   times as long, and either at most 32 of them or R large enough for the
+ *                   data type)
  *   "rows_col_blocks"  that schedule only: 16-entry blocks of the column space per
  *                   wavefront (1..4), 0 = chosen by the planner
  *   "inner_splits"  pieces the sweep over the inner column mode is cut into (1..64),

@@ -526,7 +526,7 @@ def test_paired_rows_for_the_first_two_modes(mt, oracle, dtype):
               ((31, 7, 50), 17, 0), ((1, 40, 90), 6, 0), ((7, 9, 11, 13, 5), 70, 0), ((17, 200, 33), 24, 0),
               ((32, 3, 500), 33, 0), ((5, 2000, 9), 3, 0))
     forced = (((64, 5, 50), 16, 1), ((128, 3, 7, 9), 5, 1), ((65, 4, 33), 70, 1), ((127, 2, 100), 20, 1), ((192, 7, 40), 8, 1),
-              ((80, 6, 3), 3, 1), ((1000, 3, 17), 9, 1), ((16, 16, 50), 16, 0), ((16, 16, 50), 16, 1), ((32, 8, 70), 20, 0),
+              ((80, 6, 3), 3, 1), ((1000, 3, 40), 9, 1), ((16, 16, 50), 16, 0), ((16, 16, 50), 16, 1), ((32, 8, 70), 20, 0),
               # first mode of more than 32 entries: the weighted tiles are stored whole
               ((40, 30, 20, 9), 16, 0), ((129, 9, 40, 7), 10, 0), ((50, 7, 300), 33, 0), ((100, 5, 9, 11), 70, 0),
               ((64, 5, 50), 16, 0), ((401, 21, 12, 11), 32, 0), ((33, 2, 500), 5, 0))
